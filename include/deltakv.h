@@ -1,0 +1,193 @@
+/*
+ * deltakv -- delta-prefill attention over a pooled, prefix-aliased KV cache (MI355X / gfx950).
+ *
+ * C ABI of the library.  Plain C types only.  Every pointer argument is marked
+ * HOST or DEVICE.  Device buffers are allocated and owned by the caller; the
+ * library owns host metadata and a small ring of pinned host staging buffers.
+ *
+ * General rules
+ *   - every function returns an int32_t status (DK_OK == 0, errors negative), never
+ *     throws, aborts or prints;
+ *   - a call that fails leaves the pool's state unchanged;
+ *   - calls that launch GPU work (dk_kv_append, dk_delta_attend, dk_seq_gather) are
+ *     asynchronous on the HIP stream passed as `stream` (a hipStream_t cast to void*,
+ *     NULL = the default stream) and never synchronise the device.  They read the
+ *     slot metadata at call time, so later host-side calls (trim, release, alias) do
+ *     not affect work already enqueued.  All GPU-launching calls on one pool must be
+ *     issued on one stream, or be ordered by the caller;
+ *   - host-only calls are thread-safe (one mutex per pool, paper Sec. 3.1).
+ *
+ * Vocabulary (paper Sec. 2.2, 3.1, 3.3): a *slot* is one named sequence sigma_i of the
+ * pool; a *cell* holds one token's K and V for all KV heads; n is the number of tokens a
+ * slot already caches, Delta the number of new tokens of this call.
+ */
+#ifndef DELTAKV_H
+#define DELTAKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dk_pool dk_pool; /* opaque */
+
+enum { DK_F32 = 0, DK_BF16 = 1 };
+
+enum {
+  DK_OK = 0,
+  DK_ERR_INVALID = -1,     /* bad argument or a state the call does not allow */
+  DK_ERR_TIMEOUT = -2,     /* dk_seq_acquire: no free slot within the timeout */
+  DK_ERR_NO_CELLS = -3,    /* the arena cannot hold the cells an append needs */
+  DK_ERR_NO_SLOT = -4,     /* slot id out of range or not acquired */
+  DK_ERR_DUP_SLOT = -5,    /* the same slot listed twice in one batched call */
+  DK_ERR_UNSUPPORTED = -6, /* shape / dtype / alias form the library does not implement */
+  DK_ERR_WORKSPACE = -7,   /* workspace missing or too small */
+  DK_ERR_HIP = -8          /* a HIP runtime call failed (see dk_last_hip_error) */
+};
+
+/*
+ * Pool description (paper Sec. 3.1: one unified inference context allocated once, whose
+ * sequence-id space is a fixed pool split into a transient and a session region).
+ *
+ * Arena layout, DEVICE memory, caller-owned, must outlive the pool:
+ *   k_arena[kv_head][cell][d], v_arena[kv_head][cell][d]   (head-major, d contiguous)
+ *   each arena_cells * n_kv_heads * head_dim elements of `dtype`, 256-byte aligned.
+ * Cells are handed out in granules of `granule_cells` consecutive cells (0 selects 256);
+ * arena_cells is rounded down to whole granules.
+ * Slot ids [0, n_slots - n_session_slots) form the transient region, the rest the
+ * session region.
+ * dev_meta: DEVICE scratch of at least dk_meta_bytes() bytes, caller-owned, used for
+ * the per-call copy tables of dk_kv_append / dk_seq_gather.
+ */
+typedef struct {
+  int32_t n_slots;
+  int32_t n_session_slots;
+  int64_t arena_cells;
+  int32_t granule_cells;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t dtype; /* DK_F32 or DK_BF16: element type of the arena, Q, K/V inputs and O */
+  void* k_arena; /* DEVICE */
+  void* v_arena; /* DEVICE */
+  void* dev_meta; /* DEVICE */
+  int64_t dev_meta_bytes;
+} dk_pool_desc;
+
+/* Bytes of dev_meta a pool of this description needs.  HOST only. */
+int32_t dk_meta_bytes(const dk_pool_desc* desc, int64_t* bytes_out);
+
+/*
+ * pool_create (paper Sec. 3.1).  Builds the slot table, the two free lists and the cell
+ * allocator.  Touches no device memory.  DK_ERR_INVALID on a malformed description,
+ * DK_ERR_UNSUPPORTED for head_dim not in {64, 128}, n_q_heads not a multiple of
+ * n_kv_heads, or an unknown dtype.
+ */
+int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out);
+int32_t dk_pool_destroy(dk_pool* pool);
+
+/*
+ * Slot lifecycle (paper Sec. 3.1: acquire from the region's free list, block with a
+ * configurable timeout when it is empty, return the slot on completion).
+ * region: 0 transient, 1 session.  timeout_ms < 0 waits without limit, 0 polls.
+ * dk_seq_release empties the slot and returns it to its region's free list; cells that an
+ * alias still references stay intact until the last reference goes (Sec. 3.3: a trie node
+ * names the donor whose state still holds the matched cells).
+ */
+int32_t dk_seq_acquire(dk_pool* pool, int32_t region, int64_t timeout_ms, int32_t* slot_out);
+int32_t dk_seq_release(dk_pool* pool, int32_t slot);
+int32_t dk_seq_len(dk_pool* pool, int32_t slot, int64_t* len_out);
+
+/*
+ * seq_alias: SeqAlias(donor, dst, 0, m) of paper Alg. 1 / Sec. 3.3.  Metadata only: dst's
+ * positions [0, p1) become the donor's cells; no K/V byte is read or written and the
+ * cost does not depend on p1.  Requires p0 == 0 (else DK_ERR_UNSUPPORTED), donor != dst,
+ * 0 <= p1 <= len(donor) and len(dst) == 0 (else DK_ERR_INVALID).  p1 == 0 is a no-op.
+ * Afterwards donor and dst grow independently: each one's appends are invisible to the other.
+ */
+int32_t dk_seq_alias(dk_pool* pool, int32_t donor, int32_t dst, int64_t p0, int64_t p1);
+
+/*
+ * seq_trim: roll a slot back to new_len <= len tokens (paper Alg. 2, last step: drop the
+ * rejected speculative tokens).  Metadata only.  Cells other slots still see are kept.
+ */
+int32_t dk_seq_trim(dk_pool* pool, int32_t slot, int64_t new_len);
+
+/*
+ * kv_append: write new tokens' K and V into the slots' next cells (the cache write of
+ * Decode(sigma, batch) in paper Alg. 1 / Alg. 2; only the delta cells are committed).
+ *   slots     HOST  [n_seqs]     distinct acquired slot ids
+ *   cu_delta  HOST  [n_seqs+1]   cu_delta[0] == 0, non-decreasing; entry b owns packed
+ *                                token rows cu_delta[b] .. cu_delta[b+1]-1
+ *   n_accept  HOST  [n_seqs] or NULL: append only the first n_accept[b] tokens of entry b
+ *                                (speculative verify: 1 + accepted drafts)
+ *   k_new, v_new  DEVICE [cu_delta[n_seqs], n_kv_heads, head_dim] token-major, contiguous
+ * On success len(slot_b) grows by the appended count.  DK_ERR_NO_CELLS if the arena cannot
+ * hold all of them (nothing is written, no length changes).
+ */
+int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                     const int32_t* n_accept, const void* k_new, const void* v_new, void* stream);
+
+/*
+ * kv_reserve: the bookkeeping half of dk_kv_append without the copy, for callers whose own kernels
+ * write K/V straight into the arena (e.g. a fused projection epilogue).  Same arguments and errors
+ * as dk_kv_append; cells_out HOST int64 [cu_delta[n_seqs]] receives the destination cell of every
+ * token (-1 for tokens beyond n_accept).  HOST only, launches nothing.
+ */
+int32_t dk_kv_reserve(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                      const int32_t* n_accept, int64_t* cells_out);
+
+/*
+ * delta_attend: for every entry b and each of its Delta_b new tokens i, causal softmax
+ * attention of the token's query heads over the slot's n_b cached tokens plus new tokens
+ * 0..i (absolute positions 0 .. n_b+i), query head h reading KV head h / (n_q_heads /
+ * n_kv_heads).  Covers the batched variable-length delta prefill of paper Alg. 1 and the
+ * Delta = k+1 verification batch of Alg. 2.
+ *   q      DEVICE [cu_delta[n_seqs], n_q_heads, head_dim]
+ *   k_new, v_new  both NULL: "appended" mode, the Delta_b new tokens are already the last
+ *          Delta_b cells of slot b (n_b = len - Delta_b; Delta_b > len is DK_ERR_INVALID);
+ *          both non-NULL (DEVICE, layout as in dk_kv_append): "staged" mode, n_b = len and
+ *          the new tokens' K/V are read from these buffers, the cache is not modified.
+ *   scale  multiplies the raw dot products before the softmax
+ *   out    DEVICE [cu_delta[n_seqs], n_q_heads, head_dim], same dtype as q
+ *   lse    DEVICE float [cu_delta[n_seqs], n_q_heads] or NULL: natural-log-sum-exp of the
+ *          scaled scores of each row
+ *   workspace  DEVICE, 256-byte aligned, at least dk_attend_workspace_bytes() for the same
+ *          (slots, cu_delta, mode) and the same slot lengths; DK_ERR_WORKSPACE otherwise
+ * Entries with Delta_b == 0 produce no rows; n_b == 0 is legal.
+ */
+int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                                  int32_t staged, int64_t* bytes_out);
+int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                        const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                        int64_t workspace_bytes, void* stream);
+
+/*
+ * Probes used by the tests to check bookkeeping bit for bit.
+ * dk_seq_cells: physical cell index of each logical position (HOST int64 [cap]); writes
+ *   min(len, cap) entries.  Aliased positions report the donor's cells.
+ * dk_seq_gather: copy the slot's logical contents out as DEVICE [len, n_kv_heads, head_dim].
+ * dk_pool_stats: cells currently allocated to live sequences / chains, and free cells.
+ */
+int32_t dk_seq_cells(dk_pool* pool, int32_t slot, int64_t* cells_out, int64_t cap);
+int32_t dk_seq_gather(dk_pool* pool, int32_t slot, void* k_out, void* v_out, void* stream);
+int32_t dk_pool_stats(dk_pool* pool, int64_t* cells_held_out, int64_t* cells_free_out);
+
+/* Kernel selection for dk_delta_attend: 0 automatic (default), 1 force the scalar reference kernel. */
+int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
+/*
+ * Device time of the attention kernels (not the merge kernel) of the most recent dk_delta_attend on
+ * this pool, measured with HIP events on the call's stream; waits for that work to finish.
+ * Recording is off until dk_set_attend_timing(pool, 1).  ms_out HOST float.
+ */
+int32_t dk_set_attend_timing(dk_pool* pool, int32_t enable);
+int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out);
+
+const char* dk_strerror(int32_t status);
+int32_t dk_last_hip_error(dk_pool* pool);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTAKV_H */

@@ -1,0 +1,222 @@
+"""ctypes binding of libdeltakv: argument marshalling only.
+
+Function names mirror the C ABI (include/deltakv.h) without the dk_ prefix.  Device memory and
+streams come from PyTorch; nothing is computed here.  If the shared library has not been built,
+every call raises: there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdeltakv.so")
+
+F32, BF16 = 0, 1
+OK = 0
+STATUS_NAMES = {0: "OK", -1: "INVALID", -2: "TIMEOUT", -3: "NO_CELLS", -4: "NO_SLOT", -5: "DUP_SLOT",
+                -6: "UNSUPPORTED", -7: "WORKSPACE", -8: "HIP"}
+
+
+class DeltaKVError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        self.name = STATUS_NAMES.get(status, str(status))
+        super().__init__(f"{where}: {self.name} ({detail})" if detail else f"{where}: {self.name}")
+
+
+class PoolDesc(C.Structure):
+    _fields_ = [("n_slots", C.c_int32), ("n_session_slots", C.c_int32), ("arena_cells", C.c_int64),
+                ("granule_cells", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("dtype", C.c_int32), ("k_arena", C.c_void_p), ("v_arena", C.c_void_p),
+                ("dev_meta", C.c_void_p), ("dev_meta_bytes", C.c_int64)]
+
+
+_lib = None
+
+_I32P = C.POINTER(C.c_int32)
+_I64P = C.POINTER(C.c_int64)
+
+SIGNATURES = {
+    "dk_meta_bytes": (C.c_int32, [C.POINTER(PoolDesc), _I64P]),
+    "dk_pool_create": (C.c_int32, [C.POINTER(PoolDesc), C.POINTER(C.c_void_p)]),
+    "dk_pool_destroy": (C.c_int32, [C.c_void_p]),
+    "dk_seq_acquire": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64, _I32P]),
+    "dk_seq_release": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_seq_len": (C.c_int32, [C.c_void_p, C.c_int32, _I64P]),
+    "dk_seq_alias": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64]),
+    "dk_seq_trim": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64]),
+    "dk_kv_append": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dk_kv_reserve": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, _I64P]),
+    "dk_attend_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_int32, _I64P]),
+    "dk_delta_attend": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
+    "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
+    "dk_seq_gather": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dk_pool_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P]),
+    "dk_set_attend_variant": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_set_attend_timing": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_last_attend_ms": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float)]),
+    "dk_strerror": (C.c_char_p, [C.c_int32]),
+    "dk_last_hip_error": (C.c_int32, [C.c_void_p]),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_26289_amd.build` "
+                "(there is no CPU fallback)")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(rc: int, where: str, pool=None):
+    if rc != OK:
+        detail = ""
+        if rc == -8 and pool is not None:
+            detail = f"hipError {lib().dk_last_hip_error(pool)}"
+        raise DeltaKVError(rc, where, detail)
+
+
+def _i32(values: Optional[Sequence[int]]):
+    if values is None:
+        return None, None
+    arr = np.ascontiguousarray(values, dtype=np.int32)
+    return arr, arr.ctypes.data_as(_I32P)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+    return h or None
+
+
+# --------------------------------------------------------------------------- pool
+def meta_bytes(desc: PoolDesc) -> int:
+    out = C.c_int64()
+    _check(lib().dk_meta_bytes(C.byref(desc), C.byref(out)), "meta_bytes")
+    return out.value
+
+
+def pool_create(desc: PoolDesc) -> C.c_void_p:
+    out = C.c_void_p()
+    _check(lib().dk_pool_create(C.byref(desc), C.byref(out)), "pool_create")
+    return out
+
+
+def pool_destroy(pool) -> None:
+    _check(lib().dk_pool_destroy(pool), "pool_destroy")
+
+
+def seq_acquire(pool, region: int = 0, timeout_ms: int = 0) -> int:
+    out = C.c_int32()
+    _check(lib().dk_seq_acquire(pool, region, timeout_ms, C.byref(out)), "seq_acquire")
+    return out.value
+
+
+def seq_release(pool, slot: int) -> None:
+    _check(lib().dk_seq_release(pool, slot), "seq_release")
+
+
+def seq_len(pool, slot: int) -> int:
+    out = C.c_int64()
+    _check(lib().dk_seq_len(pool, slot, C.byref(out)), "seq_len")
+    return out.value
+
+
+def seq_alias(pool, donor: int, dst: int, p0: int, p1: int) -> None:
+    _check(lib().dk_seq_alias(pool, donor, dst, p0, p1), "seq_alias")
+
+
+def seq_trim(pool, slot: int, new_len: int) -> None:
+    _check(lib().dk_seq_trim(pool, slot, new_len), "seq_trim")
+
+
+def seq_cells(pool, slot: int) -> np.ndarray:
+    n = seq_len(pool, slot)
+    out = np.full(n, -1, dtype=np.int64)
+    _check(lib().dk_seq_cells(pool, slot, out.ctypes.data_as(_I64P), n), "seq_cells")
+    return out
+
+
+def pool_stats(pool):
+    held, free = C.c_int64(), C.c_int64()
+    _check(lib().dk_pool_stats(pool, C.byref(held), C.byref(free)), "pool_stats")
+    return held.value, free.value
+
+
+# --------------------------------------------------------------------------- GPU calls
+def kv_append(pool, slots, cu_delta, k_new, v_new, n_accept=None, stream=None) -> None:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    a_arr, a_p = _i32(n_accept)
+    _check(lib().dk_kv_append(pool, len(s_arr), s_p, c_p, a_p, _ptr(k_new), _ptr(v_new), _stream(stream)),
+           "kv_append", pool)
+
+
+def kv_reserve(pool, slots, cu_delta, n_accept=None) -> np.ndarray:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    a_arr, a_p = _i32(n_accept)
+    out = np.full(int(c_arr[-1]) if len(c_arr) else 0, -2, dtype=np.int64)
+    _check(lib().dk_kv_reserve(pool, len(s_arr), s_p, c_p, a_p, out.ctypes.data_as(_I64P)), "kv_reserve")
+    return out
+
+
+def attend_workspace_bytes(pool, slots, cu_delta, staged: bool) -> int:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    out = C.c_int64()
+    _check(lib().dk_attend_workspace_bytes(pool, len(s_arr), s_p, c_p, int(staged), C.byref(out)),
+           "attend_workspace_bytes", pool)
+    return out.value
+
+
+def delta_attend(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=None, lse=None,
+                 workspace=None, stream=None) -> None:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new), float(scale),
+                                 _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)),
+           "delta_attend", pool)
+
+
+def seq_gather(pool, slot: int, k_out, v_out, stream=None) -> None:
+    _check(lib().dk_seq_gather(pool, slot, _ptr(k_out), _ptr(v_out), _stream(stream)), "seq_gather", pool)
+
+
+def set_attend_variant(pool, variant: int) -> None:
+    _check(lib().dk_set_attend_variant(pool, variant), "set_attend_variant")
+
+
+def set_attend_timing(pool, enable: bool) -> None:
+    _check(lib().dk_set_attend_timing(pool, int(enable)), "set_attend_timing")
+
+
+def last_attend_ms(pool) -> float:
+    out = C.c_float()
+    _check(lib().dk_last_attend_ms(pool, C.byref(out)), "last_attend_ms", pool)
+    return out.value
+
+
+def strerror(status: int) -> str:
+    return lib().dk_strerror(status).decode()

@@ -1,0 +1,392 @@
+// C ABI of libdeltakv (see include/deltakv.h): argument checking, host bookkeeping, descriptor
+// upload and kernel launches.  Nothing here synchronises the device except the reuse guard of the
+// pinned staging ring and dk_last_attend_ms.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/deltakv.h"
+#include "kernels.hpp"
+#include "plan.hpp"
+#include "pool.hpp"
+
+namespace {
+
+constexpr int64_t kMetaBytes = 1 << 20;  // device scratch for copy tables: 256k tokens per launch
+constexpr int kRing = 4;
+
+struct Staging {
+  void* host = nullptr;
+  size_t cap = 0;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+
+int32_t env_int(const char* name, int32_t dflt) {
+  const char* v = std::getenv(name);
+  return (v && *v) ? std::atoi(v) : dflt;
+}
+
+}  // namespace
+
+struct dk_pool {
+  dk_pool_desc desc;
+  dk::Pool meta;
+  dk::PlanConfig cfg;
+  Staging ring[kRing];
+  int ring_next = 0;
+  int32_t variant = 0;
+  int32_t timing = 0;
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  bool timed = false;
+  int32_t last_hip = 0;
+  std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring and dev_meta)
+
+  dk_pool(const dk_pool_desc& d, int32_t granule)
+      : desc(d), meta(d.n_slots, d.n_session_slots, d.arena_cells, granule) {}
+
+  dk::ArenaView view() const {
+    return {desc.k_arena, desc.v_arena, meta_arena_cells, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.dtype};
+  }
+  int64_t meta_arena_cells = 0;
+
+  int32_t hip_fail(hipError_t e) {
+    last_hip = (int32_t)e;
+    return DK_ERR_HIP;
+  }
+
+  // A pinned host buffer of at least `bytes`, safe to overwrite (its previous upload has finished).
+  int32_t stage(size_t bytes, Staging** out) {
+    Staging& s = ring[ring_next];
+    ring_next = (ring_next + 1) % kRing;
+    if (!s.done) {
+      hipError_t e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    if (s.in_flight) {
+      hipError_t e = hipEventSynchronize(s.done);
+      if (e != hipSuccess) return hip_fail(e);
+      s.in_flight = false;
+    }
+    if (s.cap < bytes) {
+      if (s.host) (void)hipHostFree(s.host);
+      s.host = nullptr;
+      s.cap = 0;
+      size_t cap = 1 << 16;
+      while (cap < bytes) cap <<= 1;
+      hipError_t e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
+      if (e != hipSuccess) return hip_fail(e);
+      s.cap = cap;
+    }
+    *out = &s;
+    return DK_OK;
+  }
+
+  int32_t upload(Staging* s, void* dev, size_t bytes, hipStream_t stream) {
+    hipError_t e = hipMemcpyAsync(dev, s->host, bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hipEventRecord(s->done, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    s->in_flight = true;
+    return DK_OK;
+  }
+};
+
+namespace {
+
+bool desc_ok(const dk_pool_desc* d, int32_t* why) {
+  *why = DK_ERR_INVALID;
+  if (!d || d->n_slots <= 0 || d->n_session_slots < 0 || d->n_session_slots > d->n_slots) return false;
+  if (d->granule_cells < 0 || d->arena_cells <= 0) return false;
+  if (d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0) return false;
+  *why = DK_ERR_UNSUPPORTED;
+  if (d->n_q_heads % d->n_kv_heads) return false;
+  if (d->head_dim != 64 && d->head_dim != 128) return false;
+  if (d->dtype != DK_F32 && d->dtype != DK_BF16) return false;
+  return true;
+}
+
+bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t dk_meta_bytes(const dk_pool_desc* desc, int64_t* bytes_out) {
+  int32_t why;
+  if (!bytes_out) return DK_ERR_INVALID;
+  if (!desc_ok(desc, &why)) return why;
+  *bytes_out = kMetaBytes;
+  return DK_OK;
+}
+
+int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
+  int32_t why;
+  if (!pool_out) return DK_ERR_INVALID;
+  *pool_out = nullptr;
+  if (!desc_ok(desc, &why)) return why;
+  if (!desc->k_arena || !desc->v_arena || !desc->dev_meta || desc->dev_meta_bytes < kMetaBytes) return DK_ERR_INVALID;
+  if (((uintptr_t)desc->k_arena | (uintptr_t)desc->v_arena | (uintptr_t)desc->dev_meta) & 255) return DK_ERR_INVALID;
+  const int32_t granule = desc->granule_cells ? desc->granule_cells : 256;
+  if (desc->arena_cells / granule <= 0) return DK_ERR_INVALID;
+  if (desc->arena_cells > INT32_MAX) return DK_ERR_UNSUPPORTED;
+  dk_pool* p = new (std::nothrow) dk_pool(*desc, granule);
+  if (!p) return DK_ERR_INVALID;
+  // The arena keeps the caller's stride: rows of KV head g start at g * arena_cells.
+  p->meta_arena_cells = desc->arena_cells;
+  const int32_t group = desc->n_q_heads / desc->n_kv_heads;
+  dk::PlanConfig& c = p->cfg;
+  c.n_q_heads = desc->n_q_heads;
+  c.n_kv_heads = desc->n_kv_heads;
+  c.head_dim = desc->head_dim;
+  c.use_mfma = desc->dtype == DK_BF16 && desc->head_dim == 128 && is_pow2(group) && group <= 16;
+  c.tile_rows = 256;
+  c.stream_rows = 64;
+  c.kv_tile = 64;
+  c.tile_target = env_int("DELTAKV_TILE_TARGET", 3 * 256 / desc->n_kv_heads);
+  c.stream_target = env_int("DELTAKV_STREAM_TARGET", 8 * 256 / desc->n_kv_heads);
+  c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 1024);
+  c.stream_min_chunk = env_int("DELTAKV_STREAM_MIN_CHUNK", 512);
+  if (c.tile_target < 1) c.tile_target = 1;
+  if (c.stream_target < 1) c.stream_target = 1;
+  *pool_out = p;
+  return DK_OK;
+}
+
+int32_t dk_pool_destroy(dk_pool* pool) {
+  if (!pool) return DK_ERR_INVALID;
+  for (Staging& s : pool->ring) {
+    if (s.in_flight) (void)hipEventSynchronize(s.done);
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.done) (void)hipEventDestroy(s.done);
+  }
+  if (pool->t0) (void)hipEventDestroy(pool->t0);
+  if (pool->t1) (void)hipEventDestroy(pool->t1);
+  delete pool;
+  return DK_OK;
+}
+
+int32_t dk_seq_acquire(dk_pool* pool, int32_t region, int64_t timeout_ms, int32_t* slot_out) {
+  if (!pool) return DK_ERR_INVALID;
+  return pool->meta.acquire(region, timeout_ms, slot_out);
+}
+int32_t dk_seq_release(dk_pool* pool, int32_t slot) { return pool ? pool->meta.release(slot) : DK_ERR_INVALID; }
+int32_t dk_seq_len(dk_pool* pool, int32_t slot, int64_t* len_out) {
+  return pool ? pool->meta.length(slot, len_out) : DK_ERR_INVALID;
+}
+int32_t dk_seq_alias(dk_pool* pool, int32_t donor, int32_t dst, int64_t p0, int64_t p1) {
+  return pool ? pool->meta.alias(donor, dst, p0, p1) : DK_ERR_INVALID;
+}
+int32_t dk_seq_trim(dk_pool* pool, int32_t slot, int64_t new_len) {
+  return pool ? pool->meta.trim(slot, new_len) : DK_ERR_INVALID;
+}
+int32_t dk_seq_cells(dk_pool* pool, int32_t slot, int64_t* cells_out, int64_t cap) {
+  return pool ? pool->meta.cells(slot, cells_out, cap) : DK_ERR_INVALID;
+}
+int32_t dk_pool_stats(dk_pool* pool, int64_t* held, int64_t* free_cells) {
+  return pool ? pool->meta.stats(held, free_cells) : DK_ERR_INVALID;
+}
+
+int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                     const int32_t* n_accept, const void* k_new, const void* v_new, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+  if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
+  std::vector<int64_t> dst;
+  int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst);
+  if (rc != DK_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t per_launch = pool->desc.dev_meta_bytes / (int64_t)sizeof(int32_t);
+  for (int64_t base = 0; base < total; base += per_launch) {
+    const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);
+    Staging* s;
+    rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+    if (rc != DK_OK) return rc;
+    int32_t* h = (int32_t*)s->host;
+    for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)dst[base + t];
+    rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+    if (rc != DK_OK) return rc;
+    hipError_t e = dk::launch_kv_scatter(pool->view(), pool->desc.k_arena, pool->desc.v_arena,
+                                         (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  return DK_OK;
+}
+
+int32_t dk_kv_reserve(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                      const int32_t* n_accept, int64_t* cells_out) {
+  if (!pool) return DK_ERR_INVALID;
+  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+  if (total > 0 && !cells_out) return DK_ERR_INVALID;
+  std::vector<int64_t> dst;
+  int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst);
+  if (rc != DK_OK) return rc;
+  for (int64_t t = 0; t < total; ++t) cells_out[t] = dst[t];
+  return DK_OK;
+}
+
+int32_t dk_seq_gather(dk_pool* pool, int32_t slot, void* k_out, void* v_out, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  int64_t len = 0;
+  int32_t rc = pool->meta.length(slot, &len);
+  if (rc != DK_OK) return rc;
+  if (len == 0) return DK_OK;
+  if (!k_out || !v_out) return DK_ERR_INVALID;
+  std::vector<int64_t> cells(len);
+  rc = pool->meta.cells(slot, cells.data(), len);
+  if (rc != DK_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t per_launch = pool->desc.dev_meta_bytes / (int64_t)sizeof(int32_t);
+  for (int64_t base = 0; base < len; base += per_launch) {
+    const int32_t n = (int32_t)std::min<int64_t>(per_launch, len - base);
+    Staging* s;
+    rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+    if (rc != DK_OK) return rc;
+    int32_t* h = (int32_t*)s->host;
+    for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)cells[base + t];
+    rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+    if (rc != DK_OK) return rc;
+    hipError_t e = dk::launch_kv_gather(pool->view(), (const int32_t*)pool->desc.dev_meta, base, n, k_out, v_out, st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  return DK_OK;
+}
+
+int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                                  int32_t staged, int64_t* bytes_out) {
+  if (!pool || !bytes_out) return DK_ERR_INVALID;
+  dk::AttendPlan plan;
+  dk::PlanConfig cfg = pool->cfg;
+  if (pool->variant == 1) cfg.use_mfma = false;
+  std::lock_guard<std::mutex> lk(pool->meta.mutex());
+  int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged != 0, &plan);
+  if (rc != DK_OK) return rc;
+  *bytes_out = (int64_t)plan.total_bytes;
+  return DK_OK;
+}
+
+int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                        const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                        int64_t workspace_bytes, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  if ((k_new == nullptr) != (v_new == nullptr)) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  const bool staged = k_new != nullptr;
+  dk::AttendPlan plan;
+  dk::PlanConfig cfg = pool->cfg;
+  if (pool->variant == 1) cfg.use_mfma = false;
+  {
+    std::lock_guard<std::mutex> lk(pool->meta.mutex());
+    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged, &plan);
+    if (rc != DK_OK) return rc;
+  }
+  if (plan.total_tokens == 0) return DK_OK;
+  if (!q || !out) return DK_ERR_INVALID;
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)plan.total_bytes) return DK_ERR_WORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  Staging* s;
+  int32_t rc = pool->stage(plan.blob_bytes, &s);
+  if (rc != DK_OK) return rc;
+  char* h = (char*)s->host;
+  auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
+  put(plan.off_entries, plan.entries.data(), plan.entries.size() * sizeof(DkEntry));
+  put(plan.off_segs, plan.segs.data(), plan.segs.size() * sizeof(DkSeg));
+  put(plan.off_tile, plan.tile_items.data(), plan.tile_items.size() * sizeof(DkItem));
+  put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
+  put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
+  rc = pool->upload(s, workspace, plan.blob_bytes, st);
+  if (rc != DK_OK) return rc;
+
+  char* ws = (char*)workspace;
+  dk::AttendArgs a;
+  a.arena = pool->view();
+  a.entries = (const DkEntry*)(ws + plan.off_entries);
+  a.n_entries = (int32_t)plan.entries.size();
+  a.segs = (const DkSeg*)(ws + plan.off_segs);
+  a.q = q;
+  a.k_new = k_new;
+  a.v_new = v_new;
+  a.out = out;
+  a.lse = lse;
+  a.parts = (float*)(ws + plan.off_parts);
+  a.scale = scale;
+  a.total_tokens = (int32_t)plan.total_tokens;
+
+  hipError_t e = hipSuccess;
+  pool->timed = false;
+  if (pool->timing) {
+    if (!pool->t0) {
+      e = hipEventCreate(&pool->t0);
+      if (e == hipSuccess) e = hipEventCreate(&pool->t1);
+      if (e != hipSuccess) return pool->hip_fail(e);
+    }
+    e = hipEventRecord(pool->t0, st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  if (!cfg.use_mfma) {
+    e = dk::launch_attend_ref(a, st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  } else {
+    e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (int32_t)plan.tile_items.size(), st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+    e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (int32_t)plan.stream_items.size(), st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  if (pool->timing) {
+    e = hipEventRecord(pool->t1, st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+    pool->timed = true;
+  }
+  if (cfg.use_mfma) {
+    e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  return DK_OK;
+}
+
+int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant) {
+  if (!pool || variant < 0 || variant > 1) return DK_ERR_INVALID;
+  pool->variant = variant;
+  return DK_OK;
+}
+
+int32_t dk_set_attend_timing(dk_pool* pool, int32_t enable) {
+  if (!pool) return DK_ERR_INVALID;
+  pool->timing = enable ? 1 : 0;
+  return DK_OK;
+}
+
+int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out) {
+  if (!pool || !ms_out) return DK_ERR_INVALID;
+  if (!pool->timed) return DK_ERR_INVALID;
+  hipError_t e = hipEventSynchronize(pool->t1);
+  if (e != hipSuccess) return pool->hip_fail(e);
+  e = hipEventElapsedTime(ms_out, pool->t0, pool->t1);
+  if (e != hipSuccess) return pool->hip_fail(e);
+  return DK_OK;
+}
+
+const char* dk_strerror(int32_t status) {
+  switch (status) {
+    case DK_OK: return "ok";
+    case DK_ERR_INVALID: return "invalid argument or state";
+    case DK_ERR_TIMEOUT: return "no free slot within the timeout";
+    case DK_ERR_NO_CELLS: return "KV arena exhausted";
+    case DK_ERR_NO_SLOT: return "slot id out of range or not acquired";
+    case DK_ERR_DUP_SLOT: return "slot listed twice in one batch";
+    case DK_ERR_UNSUPPORTED: return "unsupported shape, dtype or alias form";
+    case DK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DK_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int32_t dk_last_hip_error(dk_pool* pool) { return pool ? pool->last_hip : 0; }
+
+}  // extern "C"

@@ -1,0 +1,47 @@
+// Launchers implemented in the .hip translation units.  All are asynchronous on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_types.h"
+
+namespace dk {
+
+struct ArenaView {
+  const void* k_arena;
+  const void* v_arena;
+  int64_t arena_cells;
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t dtype;  // 0 f32, 1 bf16
+};
+
+// dst[cell_of[t]] <- src[t] (append) or dst[t] <- src[cell_of[t]] (gather) for K and V; cell < 0 skips.
+hipError_t launch_kv_scatter(const ArenaView& a, void* k_arena, void* v_arena, const int32_t* cell_of_dev,
+                             int64_t tok_base, int32_t n_tok, const void* k_new, const void* v_new,
+                             hipStream_t stream);
+hipError_t launch_kv_gather(const ArenaView& a, const int32_t* cell_of_dev, int64_t tok_base, int32_t n_tok,
+                            void* k_out, void* v_out, hipStream_t stream);
+
+struct AttendArgs {
+  ArenaView arena;
+  const DkEntry* entries;
+  int32_t n_entries;
+  const DkSeg* segs;
+  const void* q;
+  const void* k_new;
+  const void* v_new;
+  void* out;
+  float* lse;
+  float* parts;
+  float scale;
+  int32_t total_tokens;
+};
+
+// Scalar reference kernel: one wavefront per (token, query head).  Any supported shape and dtype.
+hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream);
+// bf16 MFMA kernels (head_dim 128).
+hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
+hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
+hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, hipStream_t stream);
+
+}  // namespace dk

@@ -1,0 +1,115 @@
+#include "plan.hpp"
+
+#include <algorithm>
+
+namespace dk {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+namespace {
+struct RowTile {
+  int32_t entry, row0, nrows, kv_hi;
+};
+
+// Splits each row tile's visible key range [0, kv_hi) into nearly equal chunks so that the items of
+// one kernel have similar cost and there are about `target` of them per KV head.
+void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk,
+               std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
+  if (tiles.empty()) return;
+  int64_t total = 0;
+  for (const RowTile& t : tiles) total += t.kv_hi;
+  int64_t chunk = std::max<int64_t>(min_chunk, (total + target - 1) / target);
+  chunk = (chunk + kv_tile - 1) / kv_tile * kv_tile;
+  for (const RowTile& t : tiles) {
+    int32_t nsplit = (int32_t)((t.kv_hi + chunk - 1) / chunk);
+    // avoid a last split that is only a sliver
+    if (nsplit > 1 && t.kv_hi - (int64_t)(nsplit - 1) * chunk < chunk / 4) --nsplit;
+    int64_t each = ((t.kv_hi + nsplit - 1) / nsplit + kv_tile - 1) / kv_tile * kv_tile;
+    nsplit = (int32_t)((t.kv_hi + each - 1) / each);
+    int32_t part0 = -1;
+    if (nsplit > 1) {
+      part0 = (int32_t)*part_rows;
+      *part_rows += (int64_t)nsplit * t.nrows;
+      merges->push_back({t.entry, t.row0, t.nrows, part0, nsplit, {0, 0, 0}});
+    }
+    for (int32_t s = 0; s < nsplit; ++s) {
+      DkItem it{};
+      it.entry = t.entry;
+      it.row0 = t.row0;
+      it.nrows = t.nrows;
+      it.kv_lo = (int32_t)(s * each);
+      it.kv_hi = (int32_t)std::min<int64_t>(t.kv_hi, (s + 1) * each);
+      it.part_row0 = nsplit > 1 ? part0 + s * t.nrows : -1;
+      items->push_back(it);
+    }
+  }
+  // longest first, so the tail of the launch is made of the cheapest items
+  std::stable_sort(items->begin(), items->end(), [](const DkItem& a, const DkItem& b) {
+    return (int64_t)(a.kv_hi - a.kv_lo) * a.nrows > (int64_t)(b.kv_hi - b.kv_lo) * b.nrows;
+  });
+}
+}  // namespace
+
+int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                   bool staged, AttendPlan* p) {
+  int32_t rc = pool.check_batch(n_seqs, slots, cu_delta);
+  if (rc != OK) return rc;
+  *p = AttendPlan();
+  p->total_tokens = n_seqs ? cu_delta[n_seqs] : 0;
+  const int32_t group = cfg.n_q_heads / cfg.n_kv_heads;
+  std::vector<Extent> ext;
+  std::vector<RowTile> tile_tiles, stream_tiles;
+  for (int32_t b = 0; b < n_seqs; ++b) {
+    const int32_t delta = cu_delta[b + 1] - cu_delta[b];
+    int64_t len = 0;
+    rc = pool.extents_locked(slots[b], &ext, &len);
+    if (rc != OK) return rc;
+    if (!staged && delta > len) return ERR_INVALID;
+    if (len + delta > INT32_MAX / 2) return ERR_UNSUPPORTED;
+    DkEntry e{};
+    e.seg_begin = (int32_t)p->segs.size();
+    e.n = (int32_t)(staged ? len : len - delta);
+    e.delta = delta;
+    e.tok0 = cu_delta[b];
+    if (delta > 0) {
+      for (const Extent& x : ext) p->segs.push_back({x.cell, (int32_t)x.pos, (int32_t)x.len, 0, 0});
+      if (staged) p->segs.push_back({(int64_t)cu_delta[b], e.n, delta, 1, 0});
+    }
+    e.seg_end = (int32_t)p->segs.size();
+    p->entries.push_back(e);
+    if (delta == 0 || !cfg.use_mfma) continue;
+    const int32_t rows = group * delta;
+    const int32_t ei = (int32_t)p->entries.size() - 1;
+    if (rows <= cfg.stream_rows) {
+      stream_tiles.push_back({ei, 0, rows, e.n + delta});
+    } else {
+      for (int32_t r0 = 0; r0 < rows; r0 += cfg.tile_rows) {
+        const int32_t nr = std::min(cfg.tile_rows, rows - r0);
+        const int32_t last_tok = (r0 + nr - 1) / group;
+        tile_tiles.push_back({ei, r0, nr, e.n + last_tok + 1});
+      }
+    }
+  }
+  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, &p->tile_items, &p->merges, &p->part_rows);
+  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, &p->stream_items, &p->merges,
+            &p->part_rows);
+
+  size_t off = 0;
+  p->off_entries = off;
+  off = align_up(off + p->entries.size() * sizeof(DkEntry), 256);
+  p->off_segs = off;
+  off = align_up(off + p->segs.size() * sizeof(DkSeg), 256);
+  p->off_tile = off;
+  off = align_up(off + p->tile_items.size() * sizeof(DkItem), 256);
+  p->off_stream = off;
+  off = align_up(off + p->stream_items.size() * sizeof(DkItem), 256);
+  p->off_merges = off;
+  off = align_up(off + p->merges.size() * sizeof(DkMerge), 256);
+  p->blob_bytes = off;
+  p->off_parts = off;
+  off += (size_t)p->part_rows * cfg.n_kv_heads * (cfg.head_dim + 2) * sizeof(float);
+  p->total_bytes = align_up(off, 256) + 256;
+  return OK;
+}
+
+}  // namespace dk

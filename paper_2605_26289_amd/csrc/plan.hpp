@@ -1,0 +1,42 @@
+// Host-side planning of one dk_delta_attend call: resolves every slot's logical view into
+// segments, cuts the work into workgroup-sized items (with the key range split when there are
+// too few query rows to fill the chip) and lays the descriptors out for upload.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "device_types.h"
+#include "pool.hpp"
+
+namespace dk {
+
+struct PlanConfig {
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  bool use_mfma;          // bf16, D == 128, power-of-two group: the tiled kernels apply
+  int32_t tile_rows;      // packed query rows per workgroup of the tile kernel
+  int32_t stream_rows;    // max packed rows handled by the streaming (small-Delta) kernel
+  int32_t kv_tile;        // keys per inner step; split boundaries are multiples of it
+  int32_t tile_target;    // aimed number of items per KV head, tile kernel
+  int32_t stream_target;  // same, streaming kernel
+  int32_t tile_min_chunk, stream_min_chunk;  // smallest key range worth its own item
+};
+
+struct AttendPlan {
+  std::vector<DkEntry> entries;
+  std::vector<DkSeg> segs;
+  std::vector<DkItem> tile_items, stream_items;
+  std::vector<DkMerge> merges;
+  int64_t total_tokens = 0;
+  int64_t part_rows = 0;
+  size_t off_entries = 0, off_segs = 0, off_tile = 0, off_stream = 0, off_merges = 0;
+  size_t blob_bytes = 0;   // descriptors
+  size_t off_parts = 0;    // fp32 partial rows, each (head_dim + 2) floats per KV head
+  size_t total_bytes = 0;  // whole workspace
+};
+
+// Caller holds pool.mutex().
+int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                   bool staged, AttendPlan* plan);
+
+}  // namespace dk
