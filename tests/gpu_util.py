@@ -1,0 +1,113 @@
+"""Shared helpers of the GPU parity tests: build a device pool from a workload, run it, compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2605_26289_amd import DevicePool
+from paper_2605_26289_amd import binding as dk
+from paper_2605_26289_amd import workloads as wl
+
+ABS_TOL = 1e-2   # bf16 in / fp32 accumulate, max |gpu - oracle|
+REL_TOL = 2e-2   # max |gpu - oracle| / max(|oracle|, rms of the oracle row)
+F32_ABS_TOL = 1e-4
+
+
+def to_dev(x_f32: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x_f32))
+    return t.to("cuda", torch.bfloat16 if dtype == "bf16" else torch.float32)
+
+
+def errors(gpu: np.ndarray, ref: np.ndarray):
+    """max abs error and max error relative to max(|ref|, rms of the ref row) over the last axis."""
+    gpu = gpu.astype(np.float64)
+    diff = np.abs(gpu - ref)
+    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    rel = diff / np.maximum(np.abs(ref), rms)
+    return float(diff.max()) if diff.size else 0.0, float(rel.max()) if rel.size else 0.0
+
+
+def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", rows=None):
+    g = gpu.float().cpu().numpy()
+    if rows is not None:
+        g, ref = g[rows], ref[rows]
+    a, r = errors(g, ref)
+    assert np.isfinite(g).all(), what
+    if dtype == "f32":
+        assert a <= F32_ABS_TOL, (what, a, r)
+    else:
+        assert a <= ABS_TOL and r <= REL_TOL, (what, a, r)
+    return a, r
+
+
+class Mirror:
+    """A DevicePool plus the host copy of everything that was appended, for the oracle."""
+
+    def __init__(self, shape: wl.Shape, n_slots: int, arena_cells: int, granule: int = 0, seed: int = 0):
+        self.shape = shape
+        self.pool = DevicePool(n_slots, arena_cells, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                               shape.dtype, granule_cells=granule)
+        self.model = oracle.OraclePool(n_slots, 0)
+        self.rng = np.random.default_rng(seed)
+
+    def acquire(self):
+        s = self.pool.acquire()
+        assert s == self.model.acquire(0)
+        return s
+
+    def draw(self, count: int, heads: int):
+        return wl.normal(self.rng, (count, heads, self.shape.head_dim), self.shape.dtype)
+
+    def append(self, slots, deltas, k=None, v=None, n_accept=None):
+        cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int32)
+        if k is None:
+            k, v = self.draw(int(cu[-1]), self.shape.n_kv_heads), self.draw(int(cu[-1]), self.shape.n_kv_heads)
+        self.pool.append(slots, cu, to_dev(k, self.shape.dtype), to_dev(v, self.shape.dtype), n_accept)
+        for b, s in enumerate(slots):
+            cnt = deltas[b] if n_accept is None else n_accept[b]
+            self.model.append(s, k[cu[b]:cu[b] + cnt], v[cu[b]:cu[b] + cnt])
+        return k, v, cu
+
+    def alias(self, donor, dst, m):
+        self.pool.alias(donor, dst, m)
+        self.model.alias(donor, dst, 0, m)
+
+    def trim(self, slot, new_len):
+        self.pool.trim(slot, new_len)
+        self.model.trim(slot, new_len)
+
+    def cache(self, slot, upto=None):
+        k, v = self.model.gather(slot)
+        hkv, d = self.shape.n_kv_heads, self.shape.head_dim
+        if k is None:
+            k = np.zeros((0, hkv, d), np.float32)
+            v = np.zeros((0, hkv, d), np.float32)
+        return (k, v) if upto is None else (k[:upto], v[:upto])
+
+    def check_gather(self, slot):
+        kg, vg = self.pool.gather(slot)
+        ko, vo = self.cache(slot)
+        assert np.array_equal(kg.float().cpu().numpy(), ko) and np.array_equal(vg.float().cpu().numpy(), vo)
+
+    def attend_appended(self, slots, deltas, q, lse=False):
+        """The new tokens are already the last delta cells of every slot."""
+        cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int32)
+        qd = to_dev(q, self.shape.dtype)
+        lse_t = torch.empty((int(cu[-1]), self.shape.n_q_heads), dtype=torch.float32, device="cuda") if lse else None
+        out = self.pool.attend(slots, cu, qd, self.shape.scale, lse=lse_t)
+        return out, lse_t, cu
+
+    def oracle_appended(self, slots, deltas, q, rows_per_seq=None):
+        cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int64)
+        hkv, d = self.shape.n_kv_heads, self.shape.head_dim
+        caches, kn, vn = [], [], []
+        for b, s in enumerate(slots):
+            k, v = self.cache(s)
+            n = k.shape[0] - deltas[b]
+            caches.append((k[:n], v[:n]))
+            kn.append(k[n:])
+            vn.append(v[n:])
+        kn = np.concatenate(kn) if kn else np.zeros((0, hkv, d))
+        vn = np.concatenate(vn) if vn else np.zeros((0, hkv, d))
+        return oracle.delta_attend_batch(q, caches, kn, vn, cu, self.shape.scale, rows_per_seq)

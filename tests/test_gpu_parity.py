@@ -1,0 +1,227 @@
+"""GPU parity: the HIP library against the fp64 oracle on the same seeded inputs (needs an MI355X).
+
+Tolerances (bf16 inputs, fp32 accumulation): max abs error <= 1e-2 and max error relative to
+max(|oracle|, rms of the oracle row) <= 2e-2; fp32 pools: max abs <= 1e-4.  Bookkeeping (append
+placement, aliasing, trim) is compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_26289_amd import binding as dk
+from paper_2605_26289_amd import workloads as wl
+from gpu_util import Mirror, check_close, to_dev
+
+pytestmark = pytest.mark.gpu
+
+SMALL = wl.Shape(8, 2, 128, "bf16")
+
+
+def _run_turns(w: wl.Workload, granule=0, variant=0, check_every=1):
+    """Plays a workload turn by turn (append then attend, or staged attend then append) against the oracle."""
+    sh = w.shape
+    m = Mirror(sh, w.n_slots, w.cells_needed() + (granule or 256) * (w.n_slots + 2), granule, seed=w.seed)
+    dk.set_attend_variant(m.pool.handle, variant)
+    slots = [m.acquire() for _ in range(w.n_slots)]
+    if w.alias_prefix:
+        m.append([slots[0]], [w.alias_prefix])
+        for s in slots[1:]:
+            m.alias(slots[0], s, w.alias_prefix)
+    for s, h in zip(slots, w.history):
+        if h:
+            m.append([s], [h])
+    worst = (0.0, 0.0)
+    for ti, t in enumerate(w.turns):
+        for s, n in zip(t.slots, t.n_past):
+            assert m.pool.length(s) == n
+        total = sum(t.delta)
+        q = m.draw(total, sh.n_q_heads)
+        if not t.staged:
+            m.append(t.slots, t.delta)
+            out, lse, cu = m.attend_appended(t.slots, t.delta, q, lse=True)
+            if ti % check_every == 0 or ti == len(w.turns) - 1:
+                ref, ref_lse = m.oracle_appended(t.slots, t.delta, q)
+                a, r = check_close(out, ref, sh.dtype, f"{w.name} turn {ti}")
+                worst = (max(worst[0], a), max(worst[1], r))
+                assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+        else:
+            kn, vn = m.draw(total, sh.n_kv_heads), m.draw(total, sh.n_kv_heads)
+            cu = np.concatenate([[0], np.cumsum(t.delta)]).astype(np.int32)
+            knd, vnd = to_dev(kn, sh.dtype), to_dev(vn, sh.dtype)
+            out = m.pool.attend(t.slots, cu, to_dev(q, sh.dtype), sh.scale, knd, vnd)
+            caches = [m.cache(s) for s in t.slots]
+            ref, _ = oracle.delta_attend_batch(q, caches, kn, vn, cu, sh.scale)
+            a, r = check_close(out, ref, sh.dtype, f"{w.name} staged turn {ti}")
+            worst = (max(worst[0], a), max(worst[1], r))
+            m.append(t.slots, t.delta, kn, vn, n_accept=t.n_accept)
+            for s in t.slots[:4]:
+                m.check_gather(s)
+    m.pool.close()
+    return worst
+
+
+def test_kv_append_gather_bit_exact_with_alias_and_trim():
+    m = Mirror(SMALL, 4, 4096, granule=16, seed=1)
+    a, b, c, d = (m.acquire() for _ in range(4))
+    m.append([a], [100])
+    m.alias(a, b, 70)
+    m.append([a, b, c], [13, 40, 5])
+    m.alias(b, d, 90)
+    m.append([d, a], [33, 1], n_accept=[20, 0])
+    m.trim(a, 50)
+    m.append([a], [29])
+    for s in (a, b, c, d):
+        m.check_gather(s)
+    assert np.array_equal(m.pool.cells(b)[:70], m.pool.cells(d)[:70])
+    m.pool.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config1_fp32_single_session(variant):
+    a, r = _run_turns(wl.config1(), variant=variant)
+    assert a <= 1e-4
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config2_five_turn_agent(variant):
+    _run_turns(wl.config2(), variant=variant)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config3_scaled_coding_workflow(variant):
+    # same 35-turn structure at 1/8 of the lengths: the oracle finishes in seconds
+    _run_turns(wl.scaled(wl.config3(), 0.125), variant=variant, check_every=6)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config4_scaled_multi_agent_alias(variant):
+    _run_turns(wl.scaled(wl.config4(), 0.125), granule=64, variant=variant)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config5_scaled_spec_verify(variant):
+    _run_turns(wl.scaled(wl.config5(n_slots=16), 0.125), variant=variant)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("n,delta", [(0, 1), (0, 5), (1, 1), (63, 1), (64, 2), (65, 16), (200, 17), (3, 70), (0, 300),
+                                     (129, 64), (1000, 9), (257, 130)])
+def test_edge_shapes_appended_and_staged_agree_with_oracle(n, delta, variant):
+    sh = SMALL
+    m = Mirror(sh, 2, 4096, granule=16, seed=n * 1000 + delta)
+    dk.set_attend_variant(m.pool.handle, variant)
+    s, t = m.acquire(), m.acquire()
+    if n:
+        k0, v0, _ = m.append([s], [n])
+        m.append([t], [n], k0, v0)
+    q = m.draw(delta, sh.n_q_heads)
+    kn, vn = m.draw(delta, sh.n_kv_heads), m.draw(delta, sh.n_kv_heads)
+    # staged on slot s
+    out_s = m.pool.attend([s], [0, delta], to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
+    ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
+    check_close(out_s, ref, sh.dtype, "staged")
+    # appended on slot t
+    m.append([t], [delta], kn, vn)
+    out_a, _, _ = m.attend_appended([t], [delta], q)
+    check_close(out_a, ref, sh.dtype, "appended")
+    m.pool.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_varlen_batch_with_empty_entries_and_mixed_delta(variant):
+    sh = SMALL
+    m = Mirror(sh, 6, 8192, granule=32, seed=7)
+    dk.set_attend_variant(m.pool.handle, variant)
+    slots = [m.acquire() for _ in range(6)]
+    hist = [0, 300, 77, 1200, 5, 640]
+    for s, h in zip(slots, hist):
+        if h:
+            m.append([s], [h])
+    deltas = [3, 0, 129, 1, 0, 40]
+    order = [3, 1, 5, 0, 4, 2]
+    sl = [slots[i] for i in order]
+    dl = [deltas[i] for i in order]
+    q = m.draw(sum(dl), sh.n_q_heads)
+    m.append(sl, dl)
+    out, lse, cu = m.attend_appended(sl, dl, q, lse=True)
+    ref, ref_lse = m.oracle_appended(sl, dl, q)
+    check_close(out, ref, sh.dtype, "varlen")
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    m.pool.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_rows_sum_to_one_and_dominant_key(variant):
+    sh = SMALL
+    m = Mirror(sh, 1, 8192, seed=3)
+    dk.set_attend_variant(m.pool.handle, variant)
+    s = m.acquire()
+    n, delta = 3000, 33
+    k = m.draw(n + delta, sh.n_kv_heads)
+    v = np.ones_like(k)
+    m.append([s], [n + delta], k, v)
+    q = m.draw(delta, sh.n_q_heads)
+    out, _, _ = m.attend_appended([s], [delta], q)
+    assert np.abs(out.float().cpu().numpy() - 1.0).max() <= 2 ** -7  # softmax weights sum to 1
+    m.pool.close()
+
+
+def test_aliased_prefix_reads_equal_private_copy_bitwise():
+    sh = SMALL
+    m = Mirror(sh, 3, 8192, granule=64, seed=11)
+    a, b, c = (m.acquire() for _ in range(3))
+    k0, v0, _ = m.append([a], [700])
+    m.alias(a, b, 650)
+    m.append([c], [650], k0[:650], v0[:650])  # private copy of the same rows
+    delta = 20
+    kn, vn = m.draw(delta, sh.n_kv_heads), m.draw(delta, sh.n_kv_heads)
+    m.append([b, c], [delta, delta], np.concatenate([kn, kn]), np.concatenate([vn, vn]))
+    q = m.draw(delta, sh.n_q_heads)
+    out, _, _ = m.attend_appended([b, c], [delta, delta], np.concatenate([q, q]))
+    assert torch.equal(out[:delta], out[delta:])
+    m.pool.close()
+
+
+def test_chunked_delta_equals_one_call_within_tolerance():
+    sh = SMALL
+    m = Mirror(sh, 2, 8192, seed=13)
+    s, t = m.acquire(), m.acquire()
+    k0, v0, _ = m.append([s], [500])
+    m.append([t], [500], k0, v0)
+    delta = 96
+    q = m.draw(delta, sh.n_q_heads)
+    kn, vn = m.draw(delta, sh.n_kv_heads), m.draw(delta, sh.n_kv_heads)
+    m.append([s], [delta], kn, vn)
+    whole, _, _ = m.attend_appended([s], [delta], q)
+    parts = []
+    for i in range(0, delta, 32):
+        m.append([t], [32], kn[i:i + 32], vn[i:i + 32])
+        o, _, _ = m.attend_appended([t], [32], q[i:i + 32])
+        parts.append(o)
+    ref, _ = m.oracle_appended([s], [delta], q)
+    check_close(whole, ref, sh.dtype, "whole")
+    check_close(torch.cat(parts), ref, sh.dtype, "chunked")
+    m.pool.close()
+
+
+def test_errors_from_gpu_entry_points():
+    sh = SMALL
+    m = Mirror(sh, 2, 1024, granule=16, seed=17)
+    s = m.acquire()
+    m.append([s], [10])
+    q = to_dev(m.draw(20, sh.n_q_heads), sh.dtype)
+    out = torch.empty_like(q)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(dk.DeltaKVError, match="INVALID"):  # appended mode with delta > len
+        dk.delta_attend(m.pool.handle, [s], [0, 20], q, out, sh.scale, workspace=ws)
+    with pytest.raises(dk.DeltaKVError, match="WORKSPACE"):
+        dk.delta_attend(m.pool.handle, [s], [0, 5], q, out, sh.scale, workspace=None)
+    with pytest.raises(dk.DeltaKVError, match="DUP_SLOT"):
+        dk.delta_attend(m.pool.handle, [s, s], [0, 2, 4], q, out, sh.scale, workspace=ws)
+    with pytest.raises(dk.DeltaKVError, match="NO_CELLS"):
+        big = to_dev(m.draw(2000, sh.n_kv_heads), sh.dtype)
+        dk.kv_append(m.pool.handle, [s], [0, 2000], big, big)
+    assert m.pool.length(s) == 10
+    m.check_gather(s)
+    m.pool.close()
