@@ -17,7 +17,7 @@ SOURCES = ["pool.cpp", "plan.cpp", "abi.hip", "kernels_basic.hip", "attend_mfma.
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument",
+    "-Wno-unused-command-line-argument", "-Wno-inline-asm",
 ]
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC"]
 

@@ -279,7 +279,8 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   const bool staged = k_new != nullptr;
   dk::AttendPlan plan;
   dk::PlanConfig cfg = pool->cfg;
-  if (pool->variant == 1) cfg.use_mfma = false;
+  // the MFMA kernels take the row maximum before scaling, which needs a positive finite scale
+  if (pool->variant == 1 || !(scale > 0.f) || !(scale < 3.0e38f)) cfg.use_mfma = false;
   {
     std::lock_guard<std::mutex> lk(pool->meta.mutex());
     int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged, &plan);
