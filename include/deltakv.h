@@ -177,11 +177,15 @@ int32_t dk_pool_stats(dk_pool* pool, int64_t* cells_held_out, int64_t* cells_fre
 /* Kernel selection for dk_delta_attend: 0 automatic (default), 1 force the scalar reference kernel. */
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
 /*
- * Device time of the attention kernels (not the merge kernel) of the most recent dk_delta_attend on
- * this pool, measured with HIP events on the call's stream; waits for that work to finish.
- * Recording is off until dk_set_attend_timing(pool, 1).  ms_out HOST float.
+ * Device time of the attention kernels (not the descriptor upload, not the merge kernel) of recent
+ * dk_delta_attend calls on this pool, measured with HIP events recorded on the call's stream.
+ * dk_set_attend_timing(pool, n): keep the last n calls (0 <= n <= 256; 0 switches recording off).
+ * dk_attend_times: waits for the recorded work, then writes the durations in milliseconds, oldest
+ * first, of the last min(cap, recorded) calls to ms_out (HOST float [cap]); *n_out receives the count.
+ * dk_last_attend_ms: the most recent one; DK_ERR_INVALID if nothing was recorded.
  */
-int32_t dk_set_attend_timing(dk_pool* pool, int32_t enable);
+int32_t dk_set_attend_timing(dk_pool* pool, int32_t n_calls);
+int32_t dk_attend_times(dk_pool* pool, float* ms_out, int32_t cap, int32_t* n_out);
 int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out);
 
 const char* dk_strerror(int32_t status);

@@ -59,6 +59,7 @@ SIGNATURES = {
     "dk_pool_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P]),
     "dk_set_attend_variant": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_set_attend_timing": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "dk_attend_times": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, _I32P]),
     "dk_last_attend_ms": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float)]),
     "dk_strerror": (C.c_char_p, [C.c_int32]),
     "dk_last_hip_error": (C.c_int32, [C.c_void_p]),
@@ -208,8 +209,15 @@ def set_attend_variant(pool, variant: int) -> None:
     _check(lib().dk_set_attend_variant(pool, variant), "set_attend_variant")
 
 
-def set_attend_timing(pool, enable: bool) -> None:
-    _check(lib().dk_set_attend_timing(pool, int(enable)), "set_attend_timing")
+def set_attend_timing(pool, n_calls: int) -> None:
+    _check(lib().dk_set_attend_timing(pool, int(n_calls)), "set_attend_timing", pool)
+
+
+def attend_times(pool, cap: int = 256) -> np.ndarray:
+    out = np.zeros(cap, dtype=np.float32)
+    n = C.c_int32()
+    _check(lib().dk_attend_times(pool, out.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)), "attend_times", pool)
+    return out[: n.value].copy()
 
 
 def last_attend_ms(pool) -> float:

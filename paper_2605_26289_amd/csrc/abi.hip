@@ -3,6 +3,7 @@
 // pinned staging ring and dk_last_attend_ms.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -39,9 +40,8 @@ struct dk_pool {
   Staging ring[kRing];
   int ring_next = 0;
   int32_t variant = 0;
-  int32_t timing = 0;
-  hipEvent_t t0 = nullptr, t1 = nullptr;
-  bool timed = false;
+  std::vector<hipEvent_t> ev0, ev1;  // ring of start/stop events around the attention kernels
+  int64_t ev_calls = 0;              // calls recorded since timing was switched on
   int32_t last_hip = 0;
   std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring and dev_meta)
 
@@ -163,8 +163,8 @@ int32_t dk_pool_destroy(dk_pool* pool) {
     if (s.host) (void)hipHostFree(s.host);
     if (s.done) (void)hipEventDestroy(s.done);
   }
-  if (pool->t0) (void)hipEventDestroy(pool->t0);
-  if (pool->t1) (void)hipEventDestroy(pool->t1);
+  for (hipEvent_t e : pool->ev0) (void)hipEventDestroy(e);
+  for (hipEvent_t e : pool->ev1) (void)hipEventDestroy(e);
   delete pool;
   return DK_OK;
 }
@@ -320,14 +320,10 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   a.total_tokens = (int32_t)plan.total_tokens;
 
   hipError_t e = hipSuccess;
-  pool->timed = false;
-  if (pool->timing) {
-    if (!pool->t0) {
-      e = hipEventCreate(&pool->t0);
-      if (e == hipSuccess) e = hipEventCreate(&pool->t1);
-      if (e != hipSuccess) return pool->hip_fail(e);
-    }
-    e = hipEventRecord(pool->t0, st);
+  const bool timing = !pool->ev0.empty();
+  const size_t ev_slot = timing ? (size_t)(pool->ev_calls % (int64_t)pool->ev0.size()) : 0;
+  if (timing) {
+    e = hipEventRecord(pool->ev0[ev_slot], st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
   if (!cfg.use_mfma) {
@@ -339,10 +335,10 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
     e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (int32_t)plan.stream_items.size(), st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
-  if (pool->timing) {
-    e = hipEventRecord(pool->t1, st);
+  if (timing) {
+    e = hipEventRecord(pool->ev1[ev_slot], st);
     if (e != hipSuccess) return pool->hip_fail(e);
-    pool->timed = true;
+    ++pool->ev_calls;
   }
   if (cfg.use_mfma) {
     e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), st);
@@ -357,20 +353,45 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant) {
   return DK_OK;
 }
 
-int32_t dk_set_attend_timing(dk_pool* pool, int32_t enable) {
-  if (!pool) return DK_ERR_INVALID;
-  pool->timing = enable ? 1 : 0;
+int32_t dk_set_attend_timing(dk_pool* pool, int32_t n_calls) {
+  if (!pool || n_calls < 0 || n_calls > 256) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  for (hipEvent_t e : pool->ev0) (void)hipEventDestroy(e);
+  for (hipEvent_t e : pool->ev1) (void)hipEventDestroy(e);
+  pool->ev0.clear();
+  pool->ev1.clear();
+  pool->ev_calls = 0;
+  for (int32_t i = 0; i < n_calls; ++i) {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    if (e != hipSuccess) return pool->hip_fail(e);
+    pool->ev0.push_back(a);
+    pool->ev1.push_back(b);
+  }
+  return DK_OK;
+}
+
+int32_t dk_attend_times(dk_pool* pool, float* ms_out, int32_t cap, int32_t* n_out) {
+  if (!pool || !n_out || cap < 0 || (cap > 0 && !ms_out)) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  const int64_t ring = (int64_t)pool->ev0.size();
+  const int64_t have = std::min<int64_t>(std::min<int64_t>(pool->ev_calls, ring), cap);
+  for (int64_t i = 0; i < have; ++i) {
+    const size_t slot = (size_t)((pool->ev_calls - have + i) % ring);
+    hipError_t e = hipEventSynchronize(pool->ev1[slot]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms_out[i], pool->ev0[slot], pool->ev1[slot]);
+    if (e != hipSuccess) return pool->hip_fail(e);
+  }
+  *n_out = (int32_t)have;
   return DK_OK;
 }
 
 int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out) {
-  if (!pool || !ms_out) return DK_ERR_INVALID;
-  if (!pool->timed) return DK_ERR_INVALID;
-  hipError_t e = hipEventSynchronize(pool->t1);
-  if (e != hipSuccess) return pool->hip_fail(e);
-  e = hipEventElapsedTime(ms_out, pool->t0, pool->t1);
-  if (e != hipSuccess) return pool->hip_fail(e);
-  return DK_OK;
+  int32_t n = 0;
+  int32_t rc = dk_attend_times(pool, ms_out, 1, &n);
+  if (rc != DK_OK) return rc;
+  return n == 1 ? DK_OK : DK_ERR_INVALID;
 }
 
 const char* dk_strerror(int32_t status) {
