@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary (MFMA-regime) measurement")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device copy of this many MiB five times "
+                         "(reference reading for the HBM traffic counters)")
     return ap.parse_args()
 
 
@@ -243,8 +246,17 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_per_launch": n, "launches": 5}))
+        return
     w, turn = make_workload(args.workload)
-    keep = 0 if args.no_cpu_baseline else (w.n_slots if w.n_slots <= 16 else 12)
+    keep = 0 if args.no_cpu_baseline else min(w.n_slots, 32)
     sc = Scenario(w, turn, keep_host_slots=keep)
     step_s, kern_mean_ms, kern_med_ms = sc.run(args.steps, args.warmup)
     flops, nbytes = sc.algorithmic()
