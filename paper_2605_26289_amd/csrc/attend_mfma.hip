@@ -125,26 +125,31 @@ __device__ __forceinline__ void load_rows4(const char* gbase, uint32_t stride, i
       : "memory", "m0");
 }
 
-// A operand of S^T = K Q^T for key block kb and depth step ks: lane (row l%32, half l/32) holds
-// K[kb*32 + l%32][ks*16 + 8*(l/32) .. +7].
-__device__ __forceinline__ bf16x8 read_k_frag(const char* k_lds, int kb, int ks, int lane) {
+// A operand of S^T = K Q^T for key block kb and depth step ks: lane (row l%32, half h = l/32) holds
+// K[kb*32 + l%32][ks*16 + 8h .. +7], which the swizzle keeps in chunk (2ks + h) ^ (row & 15) of its row.
+// Because 2ks has bit 0 clear, that chunk is (2ks) ^ (h ^ (row & 15)): the per-lane part of the address
+// is computed once (k_lane_off) and each depth step only XORs in ks << 5.
+__device__ __forceinline__ uint32_t k_lane_off(int lane) {
   const int r = lane & 31;
-  const int chunk = (ks * 2 + (lane >> 5)) ^ (r & 15);
-  return *(const bf16x8*)(k_lds + (kb * 32 + r) * ROW_BYTES + chunk * 16);
+  return (uint32_t)(r * ROW_BYTES + (((lane >> 5) ^ (r & 15)) << 4));
+}
+__device__ __forceinline__ bf16x8 read_k_frag(const char* k_lds, uint32_t lane_off, int kb, int ks) {
+  return *(const bf16x8*)(k_lds + (lane_off ^ (uint32_t)(ks << 5)) + kb * (32 * ROW_BYTES));
 }
 
 // A operand of O^T = V^T P^T for key step j (16 keys) and depth block db: lane (column l%32, half
 // h = l/32) holds V[16j + 8u + 4h + e][db*32 + l%32] for u = 0,1 and e = 0..3 -- the same key order
-// in which the S^T accumulators hand over P.  Two transposing 64-bit LDS reads.
-__device__ __forceinline__ bf16x8 read_v_frag(const char* v_lds, int j, int db, int lane) {
+// in which the S^T accumulators hand over P.  Two transposing 64-bit LDS reads: within 16 lanes, lane i
+// supplies the address of row i/4, 4-column piece i%4 and receives column i of the four rows.
+// The row's chunk is ((db ^ (row & 3)) << 2) | x, so again only db << 6 is XORed per read.
+__device__ __forceinline__ uint32_t v_lane_off(int lane) {
   const int i = lane & 15, qd = lane >> 4;
-  const int h = qd >> 1;
-  const int rsub = i >> 2;                      // row inside the 4-row block == row & 3
+  const int rsub = i >> 2;                         // row inside the 4-row block == row & 3
   const int x = ((qd & 1) << 1) | ((i & 3) >> 1);  // 16-byte chunk inside the 64-byte column block
-  const int chunk = ((db ^ rsub) << 2) | x;
-  const int within = (i & 1) << 3;
-  const int row0 = 16 * j + 4 * h + rsub;
-  const char* p0 = v_lds + row0 * ROW_BYTES + chunk * 16 + within;
+  return (uint32_t)((4 * (qd >> 1) + rsub) * ROW_BYTES + (rsub << 6) + (x << 4) + ((i & 1) << 3));
+}
+__device__ __forceinline__ bf16x8 read_v_frag(const char* v_lds, uint32_t lane_off, int j, int db) {
+  const char* p0 = v_lds + (lane_off ^ (uint32_t)(db << 6)) + j * (16 * ROW_BYTES);
   const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p0);
   const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 8 * ROW_BYTES));
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -197,7 +202,7 @@ __device__ __forceinline__ void compute_tile(const char* k_lds, const char* v_ld
   for (int ks = 0; ks < 8; ++ks) {
     bf16x8 a[KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) a[kb] = read_k_frag(k_lds, kb, ks, lane);
+    for (int kb = 0; kb < KB; ++kb) a[kb] = read_k_frag(k_lds, k_lane_off(lane), kb, ks);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -258,7 +263,7 @@ __device__ __forceinline__ void compute_tile(const char* k_lds, const char* v_ld
   for (int j = 0; j < 2 * KB; ++j) {
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      const bf16x8 vf = read_v_frag(v_lds, j, db, lane);
+      const bf16x8 vf = read_v_frag(v_lds, v_lane_off(lane), j, db);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
         st.o[db][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb][j], st.o[db][mb], 0, 0, 0);
@@ -325,6 +330,175 @@ __device__ __forceinline__ void store_ml(const Ctx& c, const DkEntry& e, const D
   }
 }
 
+// ---- building blocks of the tile kernel's software pipeline -----------------------------------
+// S^T of one 32-key block: 8 depth steps, MB row blocks.
+template <int MB>
+__device__ __forceinline__ void qk_block(const char* k_lds, int kb, const bf16x8 (&qf)[MB][8], f32x16 (&s)[MB],
+                                         int lane) {
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 a = read_k_frag(k_lds, k_lane_off(lane), kb, ks);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[mb][ks], s[mb], 0, 0, 0);
+  }
+}
+
+// Masks keys the row may not see (beyond the causal limit or past the end of a ragged tile).
+template <int MB>
+__device__ __forceinline__ void mask_block(f32x16 (&s)[MB], int kb, const int (&limit)[MB], int lane, int cnt,
+                                           int pos) {
+  const int h = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int lim = min(cnt - 1, limit[mb] - pos);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (key > lim) s[mb][r] = -INFINITY;
+    }
+  }
+}
+
+// Row maximum (scaled, log2 units) of one block, completed across the two half-waves.
+template <int MB>
+__device__ __forceinline__ void rowmax_block(const f32x16 (&s)[MB], float c, float (&mx)[MB]) {
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    float v = fmaxf(s[mb][0], s[mb][1]);
+#pragma unroll
+    for (int r = 2; r < 16; ++r) v = fmaxf(v, s[mb][r]);
+    v = fmaxf(v, __shfl_xor(v, 32));
+    mx[mb] = v * c;
+  }
+}
+
+// The reference maximum only moves when some row's maximum grew by more than this (log2 units), so
+// the rescale of O is rare once the first tiles have been seen; weights then stay below 2^8.
+constexpr float RESCALE_SLACK = 8.f;
+
+// x *= f for an accumulator that must stay in the AGPR half of the register file.  The O^T accumulators
+// are only ever touched by MFMAs and by this (rare) rescale; going through an "a" constrained asm keeps
+// the compiler from moving all 128 of them to VGPRs and back on every trip of the key loop.
+__device__ __forceinline__ void scale_acc(float& x, float f) {
+  float t;
+  asm volatile(
+      "v_accvgpr_read_b32 %1, %0\n\t"
+      "v_mul_f32 %1, %1, %2\n\t"
+      "v_accvgpr_write_b32 %0, %1"
+      : "+a"(x), "=&v"(t)
+      : "v"(f));
+}
+
+// Raises the reference maxima to cover mx and rescales O and l, if any row of the wavefront needs it.
+template <int MB>
+__device__ __forceinline__ void maybe_rescale(RowState<MB>& st, const float (&mx)[MB]) {
+  bool grow = false;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) grow |= mx[mb] > st.m[mb] + RESCALE_SLACK;
+  if (__builtin_amdgcn_ballot_w64(grow) == 0) return;
+  // MFMA results must have left the matrix pipeline before the plain reads below (the compiler does not
+  // look into the asm), and the writes must have landed before the next MFMA reads them: pad generously,
+  // this path is rare.
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const float mn = fmaxf(st.m[mb], mx[mb]);
+    const float ms = (mn == -INFINITY) ? 0.f : mn;
+    const float alpha = __builtin_amdgcn_exp2f(st.m[mb] - ms);  // 1 for rows whose maximum did not move
+    st.m[mb] = mn;
+    st.l[mb] *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float x = st.o[db][mb][r];
+        scale_acc(x, alpha);
+        st.o[db][mb][r] = x;
+      }
+  }
+  asm volatile("s_nop 7" ::: "memory");
+}
+
+// Weights of one 32-key block against the current reference maxima, their sum, and the bf16 B operands.
+template <int MB>
+__device__ __forceinline__ void exp_block(f32x16 (&s)[MB], RowState<MB>& st, float c, bf16x8 (&pf)[MB][2]) {
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const float ms = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
+    float rs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][r], c, -ms));
+      rs += p;
+      s[mb][r] = p;
+    }
+    st.l[mb] += rs;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) pf[mb][j][t] = (__bf16)s[mb][8 * j + t];
+  }
+}
+
+// O^T += V^T P^T for one 32-key block (two 16-key steps).
+template <int MB>
+__device__ __forceinline__ void pv_block(const char* v_lds, int kb, const bf16x8 (&pf)[MB][2], RowState<MB>& st,
+                                         int lane) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const bf16x8 vf = read_v_frag(v_lds, v_lane_off(lane), 2 * kb + j, db);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        st.o[db][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb][j], st.o[db][mb], 0, 0, 0);
+    }
+}
+
+// One 64-key tile: S^T of both 32-key blocks (sharing every Q operand), one maximum update for the
+// tile, then weights and PV block by block, so the second block's exponentials can issue while the
+// first block's PV MFMAs run.
+template <int MB>
+__device__ __forceinline__ void tile64(const char* k_lds, const char* v_lds, const bf16x8 (&qf)[MB][8],
+                                       RowState<MB>& st, const int (&limit)[MB], float c, int lane, int cnt, int pos,
+                                       bool need_mask) {
+  f32x16 s0[MB], s1[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s0[mb][r] = s1[mb][r] = 0.f;
+  const uint32_t koff = k_lane_off(lane);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 a0 = read_k_frag(k_lds, koff, 0, ks);
+    const bf16x8 a1 = read_k_frag(k_lds, koff, 1, ks);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      s0[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[mb][ks], s0[mb], 0, 0, 0);
+      s1[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[mb][ks], s1[mb], 0, 0, 0);
+    }
+  }
+  if (need_mask) {  // wave-uniform: only diagonal and ragged tiles take this path
+    mask_block<MB>(s0, 0, limit, lane, cnt, pos);
+    mask_block<MB>(s1, 1, limit, lane, cnt, pos);
+  }
+  float mx0[MB], mx1[MB];
+  rowmax_block<MB>(s0, c, mx0);
+  rowmax_block<MB>(s1, c, mx1);
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) mx0[mb] = fmaxf(mx0[mb], mx1[mb]);
+  maybe_rescale<MB>(st, mx0);
+  bf16x8 p[MB][2];
+  exp_block<MB>(s0, st, c, p);
+  pv_block<MB>(v_lds, 0, p, st, lane);
+  exp_block<MB>(s1, st, c, p);
+  pv_block<MB>(v_lds, 1, p, st, lane);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -335,8 +509,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 // XCD's L2 when there are 8 heads), block = 256.  LDS: 2 stages x (K 16 KiB + V 16 KiB).
 // ------------------------------------------------------------------------------------------------
 constexpr int TILE_KT = 64;
+constexpr int TILE_STAGES = 3;
 constexpr int TILE_STAGE_BYTES = 2 * TILE_KT * ROW_BYTES;
-constexpr int TILE_LDS_BYTES = 2 * TILE_STAGE_BYTES;
+constexpr int TILE_LDS_BYTES = TILE_STAGES * TILE_STAGE_BYTES;
 
 __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -367,9 +542,10 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
       for (int r = 0; r < 16; ++r) st.o[db][mb][r] = 0.f;
   }
 
+  // Three LDS stages, one barrier per tile.  Iteration t: wait for this wavefront's share of tile t,
+  // barrier (every wavefront has also finished computing tile t-1, whose stage is therefore free),
+  // start the loads of tile t+2 into that stage, compute tile t.
   KvCursor cur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
-  KvTile tc, tn;
-  bool have = cur.next(c, g, TILE_KT, tc);
   auto issue = [&](const KvTile& t, int stage) {
     char* kl = smem + stage * TILE_STAGE_BYTES;
     char* vl = kl + TILE_KT * ROW_BYTES;
@@ -379,26 +555,28 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
       load_rows4<true>(t.v, t.stride, t.cnt, vl, wave + 4 * b, lane);
     }
   };
-  if (have) issue(tc, 0);
+  KvTile t0, t1, t2;  // tile being computed, next, the one after
+  bool have0 = cur.next(c, g, TILE_KT, t0);
+  bool have1 = have0 && cur.next(c, g, TILE_KT, t1);
+  if (have0) issue(t0, 0);
+  if (have1) issue(t1, 1);
   int stage = 0;
-  while (have) {
-    const bool have_next = cur.next(c, g, TILE_KT, tn);
-    if (have_next) {
-      issue(tn, stage ^ 1);
-      wait_vmcnt<8>();  // the 8 loads just issued may stay in flight; the current tile has landed
-    } else {
-      wait_vmcnt<0>();
-    }
+  while (have0) {
+    if (have1) wait_vmcnt<8>(); else wait_vmcnt<0>();  // tile t has landed; tile t+1 may still be in flight
     __builtin_amdgcn_s_barrier();
-    if (wave_active && tc.pos <= wave_max_limit) {
+    const bool have2 = have1 && cur.next(c, g, TILE_KT, t2);
+    if (have2) issue(t2, stage == 0 ? 2 : stage - 1);
+    if (wave_active && t0.pos <= wave_max_limit) {
       const char* kl = smem + stage * TILE_STAGE_BYTES;
-      const bool need_mask = tc.cnt < TILE_KT || tc.pos + TILE_KT - 1 > wave_min_limit;
-      compute_tile<MB, TILE_KT / 32>(kl, kl + TILE_KT * ROW_BYTES, qf, st, limit, c.c, lane, tc.cnt, tc.pos, need_mask);
+      const char* vl = kl + TILE_KT * ROW_BYTES;
+      const bool need_mask = t0.cnt < TILE_KT || t0.pos + TILE_KT - 1 > wave_min_limit;
+      tile64<MB>(kl, vl, qf, st, limit, c.c, lane, t0.cnt, t0.pos, need_mask);
     }
-    __builtin_amdgcn_s_barrier();
-    tc = tn;
-    have = have_next;
-    stage ^= 1;
+    t0 = t1;
+    t1 = t2;
+    have0 = have1;
+    have1 = have2;
+    stage = stage == 2 ? 0 : stage + 1;
   }
 
   float ltot[MB];

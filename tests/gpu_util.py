@@ -28,7 +28,10 @@ def errors(gpu: np.ndarray, ref: np.ndarray):
     return float(diff.max()) if diff.size else 0.0, float(rel.max()) if rel.size else 0.0
 
 
-def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", rows=None):
+def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", rows=None, scale_abs=False):
+    """scale_abs: for synthetic edge cases with only a handful of keys the outputs reach |o| ~ 3, where
+    storing O in bf16 (half-ulp 2^-8 |o|) alone exceeds 1e-2; the absolute bound is then taken relative to
+    max(1, max|o|).  The five workload configs are always checked with scale_abs=False."""
     g = gpu.float().cpu().numpy()
     if rows is not None:
         g, ref = g[rows], ref[rows]
@@ -37,7 +40,8 @@ def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", 
     if dtype == "f32":
         assert a <= F32_ABS_TOL, (what, a, r)
     else:
-        assert a <= ABS_TOL and r <= REL_TOL, (what, a, r)
+        bound = ABS_TOL * (max(1.0, float(np.abs(ref).max())) if scale_abs and ref.size else 1.0)
+        assert a <= bound and r <= REL_TOL, (what, a, r)
     return a, r
 
 
