@@ -1,0 +1,253 @@
+// Shared device code of the bf16 MFMA attention kernels (gfx950, head_dim 128): descriptor access,
+// the walk over a slot's key segments, HBM -> LDS tile loads, MFMA operand reads and result stores.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace dk {
+namespace mfma {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr;
+typedef __attribute__((address_space(1))) const void* glb_void_ptr;
+
+constexpr int D = 128;
+constexpr int ROW_BYTES = 256;
+constexpr int PS = D + 2;  // floats per partial row: D sums, running max (log2 units), weight sum
+
+// Descriptors are read through the constant address space so that uniform reads become scalar loads
+// (they must not take part in the vector-memory counter that tracks the K/V tiles in flight).
+template <typename T>
+__device__ __forceinline__ T load_desc(const T* base, int idx) {
+  static_assert(sizeof(T) % 4 == 0, "descriptor structs are made of 32-bit words");
+  typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
+  const_u32_ptr p = (const_u32_ptr)((uintptr_t)base + (size_t)idx * sizeof(T));
+  T out;
+  uint32_t* o = (uint32_t*)&out;
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(T) / 4; ++i) o[i] = p[i];
+  return out;
+}
+
+struct Ctx {
+  const DkEntry* entries;
+  const DkSeg* segs;
+  const DkItem* items;
+  const __bf16* __restrict__ q;
+  const char* __restrict__ k_arena;
+  const char* __restrict__ v_arena;
+  const char* __restrict__ k_new;
+  const char* __restrict__ v_new;
+  __bf16* __restrict__ out;
+  float* __restrict__ lse;
+  float* __restrict__ parts;
+  float c;  // softmax scale * log2(e): scores are handled in log2 units
+  int32_t n_q_heads, n_kv_heads, gshift;
+  int64_t arena_cells;
+};
+
+// A run of at most KT consecutive K/V rows, all inside one segment.
+struct KvTile {
+  const char* k;
+  const char* v;
+  uint32_t stride;  // bytes between consecutive rows
+  int32_t cnt;      // valid rows (>= 1)
+  int32_t pos;      // logical position of row 0
+};
+
+// Walks the logical key positions [p, hi) of an entry, segment by segment.
+struct KvCursor {
+  const DkSeg* segs;
+  int32_t si, se, p, hi;
+
+  __device__ bool next(const Ctx& c, int g, int kt, KvTile& t) {
+    if (p >= hi) return false;
+    DkSeg s = load_desc(segs, si);
+    while (s.pos + s.len <= p && si + 1 < se) s = load_desc(segs, ++si);
+    const int32_t off = p - s.pos;
+    t.cnt = min(kt, min(s.pos + s.len, hi) - p);
+    if (s.src == 0) {
+      const int64_t byte = ((int64_t)g * c.arena_cells + s.start + off) * ROW_BYTES;
+      t.k = c.k_arena + byte;
+      t.v = c.v_arena + byte;
+      t.stride = ROW_BYTES;
+    } else {
+      const int64_t byte = ((s.start + off) * c.n_kv_heads + g) * (int64_t)ROW_BYTES;
+      t.k = c.k_new + byte;
+      t.v = c.v_new + byte;
+      t.stride = (uint32_t)c.n_kv_heads * ROW_BYTES;
+    }
+    t.pos = p;
+    p += t.cnt;
+    return true;
+  }
+};
+
+// One wavefront moves 4 rows (1 KiB) HBM -> LDS: lane l lands at lds + 16 l, i.e. row l / 16, chunk
+// slot l % 16, and fetches the chunk that the swizzle assigns to that slot.  Rows past the end of a
+// ragged tile re-read the last valid row; their scores are masked.
+// The load is issued from inline assembly on purpose: the compiler then keeps no account of it and
+// inserts no vmcnt(0) of its own in front of later LDS reads, so a tile can stay in flight while
+// the previous one is being consumed.  Completion is awaited explicitly with wait_vmcnt<N>().
+template <bool IS_V>
+__device__ __forceinline__ void load_rows4(const char* gbase, uint32_t stride, int cnt, char* lds_region, int blk,
+                                           int lane) {
+  const int row = blk * 4 + (lane >> 4);
+  const int slot = lane & 15;
+  const int chunk = IS_V ? (slot ^ ((row & 3) << 2)) : (slot ^ (row & 15));
+  const uint32_t voff = (uint32_t)min(row, cnt - 1) * stride + chunk * 16;
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)(lds_region + blk * 1024);
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(gbase)
+      : "memory", "m0");
+}
+
+// A operand of S^T = K Q^T for key block kb and depth step ks: lane (row l%32, half h = l/32) holds
+// K[kb*32 + l%32][ks*16 + 8h .. +7], which the swizzle keeps in chunk (2ks + h) ^ (row & 15) of its row.
+// Because 2ks has bit 0 clear, that chunk is (2ks) ^ (h ^ (row & 15)): the per-lane part of the address
+// is computed once (k_lane_off) and each depth step only XORs in ks << 5.
+__device__ __forceinline__ uint32_t k_lane_off(int lane) {
+  const int r = lane & 31;
+  return (uint32_t)(r * ROW_BYTES + (((lane >> 5) ^ (r & 15)) << 4));
+}
+__device__ __forceinline__ bf16x8 read_k_frag(const char* k_lds, uint32_t lane_off, int kb, int ks) {
+  return *(const bf16x8*)(k_lds + (lane_off ^ (uint32_t)(ks << 5)) + kb * (32 * ROW_BYTES));
+}
+
+// A operand of O^T = V^T P^T for key step j (16 keys) and depth block db: lane (column l%32, half
+// h = l/32) holds V[16j + 8u + 4h + e][db*32 + l%32] for u = 0,1 and e = 0..3 -- the same key order
+// in which the S^T accumulators hand over P.  Two transposing 64-bit LDS reads: within 16 lanes, lane i
+// supplies the address of row i/4, 4-column piece i%4 and receives column i of the four rows.
+// The row's chunk is ((db ^ (row & 3)) << 2) | x, so again only db << 6 is XORed per read.
+__device__ __forceinline__ uint32_t v_lane_off(int lane) {
+  const int i = lane & 15, qd = lane >> 4;
+  const int rsub = i >> 2;                         // row inside the 4-row block == row & 3
+  const int x = ((qd & 1) << 1) | ((i & 3) >> 1);  // 16-byte chunk inside the 64-byte column block
+  return (uint32_t)((4 * (qd >> 1) + rsub) * ROW_BYTES + (rsub << 6) + (x << 4) + ((i & 1) << 3));
+}
+__device__ __forceinline__ bf16x8 read_v_frag(const char* v_lds, uint32_t lane_off, int j, int db) {
+  const char* p0 = v_lds + (lane_off ^ (uint32_t)(db << 6)) + j * (16 * ROW_BYTES);
+  const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p0);
+  const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 8 * ROW_BYTES));
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+template <int MB>
+__device__ __forceinline__ void load_q(const Ctx& c, const DkEntry& e, int g, int row_base, int last_row, int lane,
+                                       bf16x8 (&qf)[MB][8], int (&limit)[MB]) {
+  const int gmask = (1 << c.gshift) - 1;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int row = min(row_base + mb * 32 + (lane & 31), last_row);
+    const int tok = row >> c.gshift;
+    const int head = (g << c.gshift) + (row & gmask);
+    limit[mb] = e.n + tok;  // last visible absolute position (bottom-right causal alignment)
+    const __bf16* qp = c.q + ((int64_t)(e.tok0 + tok) * c.n_q_heads + head) * D + 8 * (lane >> 5);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[mb][ks] = *(const bf16x8*)(qp + ks * 16);
+  }
+  // Make the compiler wait for Q here, once, instead of at first use inside the key loop, where its
+  // vmcnt(0) would also drain the K/V tiles that are meant to stay in flight.
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(qf[mb][ks]));
+}
+
+// One K/V tile of KB*32 keys against MB*32 query rows: S^T, online softmax, O^T update.
+template <int MB>
+__device__ __forceinline__ void store_block(const Ctx& c, const DkEntry& e, const DkItem& it, int g, int row_local0,
+                                            int lane, int db, const f32x16 (&o)[MB], const float (&ltot)[MB]) {
+  const int h = lane >> 5;
+  const int gmask = (1 << c.gshift) - 1;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int rl = row_local0 + mb * 32 + (lane & 31);
+    if (rl >= it.nrows) continue;
+    if (it.part_row0 >= 0) {
+      float* p = c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * PS + db * 32 + 4 * h;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        // PS is even, so every row starts 8-byte aligned: two float2 stores
+        *(float2*)(p + 8 * r4) = make_float2(o[mb][4 * r4], o[mb][4 * r4 + 1]);
+        *(float2*)(p + 8 * r4 + 2) = make_float2(o[mb][4 * r4 + 2], o[mb][4 * r4 + 3]);
+      }
+    } else {
+      const int row = it.row0 + rl;
+      const int tok = e.tok0 + (row >> c.gshift);
+      const int head = (g << c.gshift) + (row & gmask);
+      const float inv = 1.f / ltot[mb];
+      __bf16* dst = c.out + ((int64_t)tok * c.n_q_heads + head) * D + db * 32 + 4 * h;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = (__bf16)(o[mb][4 * r4 + t] * inv);
+        *(bf16x4*)(dst + 8 * r4) = v;
+      }
+    }
+  }
+}
+
+// Running maximum and weight sum of each row (partials) or the row's log-sum-exp (final output).
+template <int MB>
+__device__ __forceinline__ void store_ml(const Ctx& c, const DkEntry& e, const DkItem& it, int g, int row_local0,
+                                         int lane, const float (&m)[MB], const float (&ltot)[MB]) {
+  if (lane >= 32) return;
+  const int gmask = (1 << c.gshift) - 1;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int rl = row_local0 + mb * 32 + lane;
+    if (rl >= it.nrows) continue;
+    if (it.part_row0 >= 0) {
+      float* p = c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * PS;
+      p[D] = m[mb];
+      p[D + 1] = ltot[mb];
+    } else if (c.lse) {
+      const int row = it.row0 + rl;
+      const int tok = e.tok0 + (row >> c.gshift);
+      const int head = (g << c.gshift) + (row & gmask);
+      c.lse[(int64_t)tok * c.n_q_heads + head] = (m[mb] + __builtin_amdgcn_logf(ltot[mb])) * 0.6931471805599453f;
+    }
+  }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+inline Ctx make_ctx(const AttendArgs& a, const DkItem* items) {
+  Ctx c;
+  c.entries = a.entries;
+  c.segs = a.segs;
+  c.items = items;
+  c.q = (const __bf16*)a.q;
+  c.k_arena = (const char*)a.arena.k_arena;
+  c.v_arena = (const char*)a.arena.v_arena;
+  c.k_new = (const char*)a.k_new;
+  c.v_new = (const char*)a.v_new;
+  c.out = (__bf16*)a.out;
+  c.lse = a.lse;
+  c.parts = a.parts;
+  c.c = a.scale * 1.4426950408889634f;
+  c.n_q_heads = a.arena.n_q_heads;
+  c.n_kv_heads = a.arena.n_kv_heads;
+  int group = a.arena.n_q_heads / a.arena.n_kv_heads, sh = 0;
+  while ((1 << sh) < group) ++sh;
+  c.gshift = sh;
+  c.arena_cells = a.arena.arena_cells;
+  return c;
+}
+
+}  // namespace mfma
+}  // namespace dk
