@@ -60,30 +60,47 @@ struct KvTile {
   int32_t pos;      // logical position of row 0
 };
 
-// Walks the logical key positions [p, hi) of an entry, segment by segment.
+// Walks the logical key positions [p, hi) of an entry, segment by segment.  The state of the segment
+// being walked (row pointers at position p, row stride, end position) is kept in a handful of scalars,
+// so the common step touches neither the segment table nor the kernel arguments.
 struct KvCursor {
   const DkSeg* segs;
   int32_t si, se, p, hi;
+  int32_t seg_end = 0;  // first position past the current segment (0: no segment loaded yet)
+  const char* k = nullptr;
+  const char* v = nullptr;
+  uint32_t stride = 0;
 
-  __device__ bool next(const Ctx& c, int g, int kt, KvTile& t) {
-    if (p >= hi) return false;
+  __device__ __forceinline__ void enter_segment(const Ctx& c, int g) {
     DkSeg s = load_desc(segs, si);
     while (s.pos + s.len <= p && si + 1 < se) s = load_desc(segs, ++si);
     const int32_t off = p - s.pos;
-    t.cnt = min(kt, min(s.pos + s.len, hi) - p);
+    seg_end = s.pos + s.len;
     if (s.src == 0) {
       const int64_t byte = ((int64_t)g * c.arena_cells + s.start + off) * ROW_BYTES;
-      t.k = c.k_arena + byte;
-      t.v = c.v_arena + byte;
-      t.stride = ROW_BYTES;
+      k = c.k_arena + byte;
+      v = c.v_arena + byte;
+      stride = ROW_BYTES;
     } else {
       const int64_t byte = ((s.start + off) * c.n_kv_heads + g) * (int64_t)ROW_BYTES;
-      t.k = c.k_new + byte;
-      t.v = c.v_new + byte;
-      t.stride = (uint32_t)c.n_kv_heads * ROW_BYTES;
+      k = c.k_new + byte;
+      v = c.v_new + byte;
+      stride = (uint32_t)c.n_kv_heads * ROW_BYTES;
     }
+  }
+
+  __device__ __forceinline__ bool next(const Ctx& c, int g, int kt, KvTile& t) {
+    if (p >= hi) return false;
+    if (p >= seg_end) enter_segment(c, g);
+    t.cnt = min(kt, min(seg_end, hi) - p);
+    t.k = k;
+    t.v = v;
+    t.stride = stride;
     t.pos = p;
     p += t.cnt;
+    const uint32_t adv = (uint32_t)t.cnt * stride;
+    k += adv;
+    v += adv;
     return true;
   }
 };

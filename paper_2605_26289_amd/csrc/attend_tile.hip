@@ -63,17 +63,6 @@ __device__ __forceinline__ void settle(f32x16& a, f32x16& b, f32x16& c, f32x16& 
 }
 __device__ __forceinline__ void settle_acc(f32x16& a) { asm volatile("s_nop 15\n\ts_nop 7" : "+a"(a)); }
 
-// x *= f for an accumulator that stays in the AGPR half of the register file.
-__device__ __forceinline__ void scale_acc(float& x, float f) {
-  float t;
-  asm volatile(
-      "v_accvgpr_read_b32 %1, %0\n\t"
-      "v_mul_f32 %1, %1, %2\n\t"
-      "v_accvgpr_write_b32 %0, %1"
-      : "+a"(x), "=&v"(t)
-      : "v"(f));
-}
-
 // The reference maximum of a row only moves when its maximum grew by more than this (log2 units):
 // after the first tiles the rescale of O is rare, and the weights stay below 2^8.
 constexpr float RESCALE_SLACK = 8.f;
@@ -90,13 +79,17 @@ __device__ __forceinline__ void mask_tile(f32x16 (&s)[2][MB], const int (&limit)
   const int h = lane >> 5;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    const int lim = min(cnt - 1, limit[mb] - pos);
+    // key > lim  <=>  (lim - 4h) - (key - 4h) < 0; done with integer sign arithmetic so that the 64
+    // decisions do not each occupy a scalar register pair
+    const int base = min(cnt - 1, limit[mb] - pos) - 4 * h;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-        if (key > lim) s[kb][mb][r] = -INFINITY;
+        const int rest = kb * 32 + 8 * (r >> 2) + (r & 3);
+        const uint32_t hide = (uint32_t)((base - rest) >> 31);  // all ones if the key is hidden
+        const uint32_t bits = __float_as_uint(s[kb][mb][r]);
+        s[kb][mb][r] = __uint_as_float((bits & ~hide) | (0xff800000u & hide));
       }
   }
 }
@@ -115,8 +108,7 @@ __device__ __forceinline__ void update_reference(const f32x16 (&s)[2][MB], WaveS
     grow |= mx[mb] > st.m[mb] + RESCALE_SLACK;
   }
   if (__builtin_amdgcn_ballot_w64(grow) == 0) return;
-  // rare: all MFMAs that wrote O have long been issued, pad anyway before touching the accumulators
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  // rare path; settle_acc() pads both the read after the last MFMA and the next MFMA after the write
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     const float mn = fmaxf(st.m[mb], mx[mb]);
@@ -124,16 +116,17 @@ __device__ __forceinline__ void update_reference(const f32x16 (&s)[2][MB], WaveS
     const float alpha = __builtin_amdgcn_exp2f(st.m[mb] - ms);  // 1 for rows whose maximum did not move
     st.m[mb] = mn;
     st.l[mb] *= alpha;
+    // whole-register arithmetic only: element-wise inserts into the accumulator tuples make the compiler
+    // shuttle all of O between the two register files on every trip of the key loop
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = st.o[db][mb][r];
-        scale_acc(x, alpha);
-        st.o[db][mb][r] = x;
-      }
+    for (int db = 0; db < 4; ++db) {
+      settle_acc(st.o[db][mb]);
+      f32x16 t = st.o[db][mb];
+      t = t * alpha;
+      st.o[db][mb] = t;
+      settle_acc(st.o[db][mb]);
+    }
   }
-  asm volatile("s_nop 7" ::: "memory");
 }
 
 // One pipeline step.  sc holds S^T of the current tile (complete), sn receives S^T of the next tile and
@@ -258,9 +251,11 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
     st.m[mb] = -INFINITY;
     st.l[mb] = 0.f;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.o[db][mb][r] = 0.f;
+    for (int db = 0; db < 4; ++db) {
+      f32x16 z = {0};
+      asm volatile("" : "+a"(z));  // born in an AGPR tuple as a whole
+      st.o[db][mb] = z;
+    }
   }
   const uint32_t koff = k_lane_off(lane), voff = v_lane_off(lane);
 
