@@ -2,17 +2,34 @@
 //
 // A workgroup owns 256 packed query rows of one KV head (4 wavefronts x 64 rows, row r = token r / G,
 // head r % G of the group) and walks the visible keys in 64-key tiles that all four wavefronts share
-// through a 4-stage LDS ring (HBM -> LDS by global_load_lds_dwordx4, one barrier per tile).
+// through LDS (HBM -> LDS by global_load_lds_dwordx4, one barrier per tile).
 //
 // Per tile and wavefront there are 64 MFMAs (32 for S^T = K Q^T, 32 for O^T += V^T P^T, all
-// v_mfma_f32_32x32x16_bf16) and 64 score elements per lane for the softmax, whose v_exp_f32 alone
-// costs about half the MFMA time.  With one wavefront per SIMD nothing else can hide that VALU work,
-// so the loop is software pipelined by hand: while the matrix pipe computes S^T of tile t+1 and then
-// PV of tile t, the VALU turns S^T of tile t into P, one or two elements after every MFMA.
+// v_mfma_f32_32x32x16_bf16) and 64 score elements per lane for the softmax.  With one wavefront per
+// SIMD the matrix pipe only stays busy if the same instruction stream feeds it while doing the
+// softmax, so the key loop is a three-stage software pipeline.  Step t issues
+//     S^T(t+1)             32 MFMAs, K tile t+1
+//     O^T += V^T P^T(t-1)  32 MFMAs, V tile t-1 and the probabilities made in step t-1
+// and, between those MFMAs, the VALU turns S^T(t) into P(t) (exp2, bf16 pack, row sums) and takes the
+// row maxima of S^T(t+1) once that is complete.  Nothing inside a step depends on anything else
+// computed in the same step, so the interleaving is a static schedule: a few VALU / LDS instructions
+// after every MFMA.
+//
+// The reference maximum of a row only has to be raised when the scores outgrow it by more than
+// RESCALE_SLACK; whether tile t needs that is known before step t starts (its maxima were taken in
+// step t-1).  Raising it is rare after the first tile and costs nothing inside the step: the weight
+// sum is rescaled on the spot, P(t) is made against the new maximum, and O -- which in step t still
+// receives P(t-1), made against the old one -- is rescaled at the top of step t+1.
+// There is one step body for everything.  Tiles on the causal diagonal or with a ragged end get their
+// hidden scores set to -inf before the step; a tile a wavefront cannot see at all (its rows end
+// earlier than those of the workgroup's other wavefronts) or that does not exist (the extra last step
+// that only has P(t-1) left to apply) is simply masked completely, so its probabilities are zero.
+// Step 0 applies a zero P to a zero-filled V stage.
 //
 // Register plan (one wavefront per SIMD, 512 registers): AGPRs hold the O^T accumulators (128) and Q
-// (64, read by the MFMAs as B operand straight from AGPRs); VGPRs hold two S^T buffers (2 x 64, the
-// MFMAs write them directly, the VALU works on them in place), P (32) and the K/V operand fragments.
+// (64, read by the MFMAs as B operand straight from AGPRs) and the K/V fragments on their way from
+// LDS; VGPRs hold two S^T buffers (2 x 64, written by the MFMAs directly) and two P buffers (2 x 32).
+// The step body exists twice with the buffer roles swapped, so nothing is copied between steps.
 // The MFMAs are issued from inline assembly so that this placement is exactly what the compiler
 // allocates; the consequence is that MFMA-result hazards are handled by hand (see settle()).
 #include <hip/hip_runtime.h>
@@ -25,35 +42,25 @@
 namespace dk {
 namespace mfma {
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
 constexpr int TILE_KT = 64;
-constexpr int TILE_STAGES = 4;
-constexpr int TILE_STAGE_BYTES = 2 * TILE_KT * ROW_BYTES;  // K 16 KiB + V 16 KiB
-constexpr int TILE_LDS_BYTES = TILE_STAGES * TILE_STAGE_BYTES;
+constexpr int TILE_RING = 3;                           // stages per ring, K and V each
+constexpr int TILE_STAGE_BYTES = TILE_KT * ROW_BYTES;  // 16 KiB
+constexpr int TILE_LDS_BYTES = 2 * TILE_RING * TILE_STAGE_BYTES;
 constexpr int MB = 2;  // 32-row blocks per wavefront
 
 // S^T accumulators live in VGPRs, O^T accumulators and Q in AGPRs.
-#ifdef DK_TILE_BUILTIN_MFMA  // diagnosis build: let the compiler place and guard the MFMAs
 __device__ __forceinline__ void mfma_s_first(f32x16& s, const bf16x8& k, const bf16x8& q) {
-  f32x16 z = {0};
-  s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k, q, z, 0, 0, 0);
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "a"(k), "a"(q));
 }
 __device__ __forceinline__ void mfma_s(f32x16& s, const bf16x8& k, const bf16x8& q) {
-  s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k, q, s, 0, 0, 0);
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "a"(k), "a"(q));
 }
-__device__ __forceinline__ void mfma_o(f32x16& o, const bf16x8& v, const bf16x8& p) {
-  o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, p, o, 0, 0, 0);
+__device__ __forceinline__ void mfma_o(f32x16& o, const bf16x8& v, const u32x4& p) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "a"(v), "v"(p));
 }
-#else
-__device__ __forceinline__ void mfma_s_first(f32x16& s, const bf16x8& k, const bf16x8& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(q));
-}
-__device__ __forceinline__ void mfma_s(f32x16& s, const bf16x8& k, const bf16x8& q) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(q));
-}
-__device__ __forceinline__ void mfma_o(f32x16& o, const bf16x8& v, const bf16x8& p) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o) : "v"(v), "v"(p));
-}
-#endif
 
 // The compiler does not see that these registers come out of the matrix pipeline, so it would not
 // insert the wait states a plain VALU read of a fresh MFMA result needs.  Every place where such a
@@ -63,9 +70,47 @@ __device__ __forceinline__ void settle(f32x16& a, f32x16& b, f32x16& c, f32x16& 
 }
 __device__ __forceinline__ void settle_acc(f32x16& a) { asm volatile("s_nop 15\n\ts_nop 7" : "+a"(a)); }
 
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+// Keeps a value's computation where the source has it: ordinary arithmetic whose only consumers are
+// in a later step would otherwise be sunk out of the MFMA schedule it is meant to fill.
+template <typename T>
+__device__ __forceinline__ void pin(T& x) {
+  asm volatile("" : "+v"(x));
+}
+// max over the two half-waves: lane l and lane l ^ 32 both get max(x[l], x[l ^ 32])
+__device__ __forceinline__ float max_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
+}
+// Two probabilities -> one register of bf16 (RNE); their sum, as rounded, goes into the weight sum so
+// that numerator and denominator of the softmax see the same weights.
+__device__ __forceinline__ uint32_t pack_add(float p0, float p1, float& l) {
+  bf16x2 w;
+  w[0] = (__bf16)p0;
+  w[1] = (__bf16)p1;
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
+  l = __builtin_amdgcn_fdot2_f32_bf16(w, ones, l, false);
+  return __builtin_bit_cast(uint32_t, w);
+}
+
 // The reference maximum of a row only moves when its maximum grew by more than this (log2 units):
 // after the first tiles the rescale of O is rare, and the weights stay below 2^8.
 constexpr float RESCALE_SLACK = 8.f;
+
+#ifdef DK_PROF  // timing build: cycles per loop section, summed over wavefronts
+__device__ unsigned long long g_prof[8];
+#define DK_PROF_T(x) const long long x = __builtin_readcyclecounter()
+#define DK_PROF_ADD(i, v) pacc[i] += (v)
+#else
+#define DK_PROF_T(x)
+#define DK_PROF_ADD(i, v)
+#endif
 
 struct WaveState {
   f32x16 o[4][MB];  // [depth block][row block], AGPR
@@ -94,105 +139,162 @@ __device__ __forceinline__ void mask_tile(f32x16 (&s)[2][MB], const int (&limit)
   }
 }
 
-// Row maxima of the tile; raises the reference maxima (and rescales O, l) if some row needs it.
-__device__ __forceinline__ void update_reference(const f32x16 (&s)[2][MB], WaveState& st, float c) {
-  float mx[MB];
-  bool grow = false;
+// Row maxima (unscaled) of one S^T tile.
+__device__ __forceinline__ void row_max(const f32x16 (&s)[2][MB], float (&mx)[MB]) {
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    float v = fmaxf(s[0][mb][0], s[1][mb][0]);
+    float v = max3(s[0][mb][0], s[1][mb][0], s[1][mb][0]);
 #pragma unroll
-    for (int r = 1; r < 16; ++r) v = fmaxf(v, fmaxf(s[0][mb][r], s[1][mb][r]));
-    v = fmaxf(v, __shfl_xor(v, 32));
-    mx[mb] = v * c;
-    grow |= mx[mb] > st.m[mb] + RESCALE_SLACK;
+    for (int r = 1; r < 16; ++r) v = max3(v, s[0][mb][r], s[1][mb][r]);
+    mx[mb] = max_halves(v);
   }
-  if (__builtin_amdgcn_ballot_w64(grow) == 0) return;
-  // rare path; settle_acc() pads both the read after the last MFMA and the next MFMA after the write
+}
+
+// O *= alpha, row by row.  Whole-register arithmetic only: element-wise inserts into the accumulator
+// tuples make the compiler shuttle all of O between the two register files on every trip of the key loop.
+// settle_acc() pads both the read after the last MFMA and the next MFMA after the write.
+__device__ __forceinline__ void rescale_o(WaveState& st, const float (&alpha)[MB]) {
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    const float mn = fmaxf(st.m[mb], mx[mb]);
-    const float ms = (mn == -INFINITY) ? 0.f : mn;
-    const float alpha = __builtin_amdgcn_exp2f(st.m[mb] - ms);  // 1 for rows whose maximum did not move
-    st.m[mb] = mn;
-    st.l[mb] *= alpha;
-    // whole-register arithmetic only: element-wise inserts into the accumulator tuples make the compiler
-    // shuttle all of O between the two register files on every trip of the key loop
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       settle_acc(st.o[db][mb]);
       f32x16 t = st.o[db][mb];
-      t = t * alpha;
+      t = t * alpha[mb];
       st.o[db][mb] = t;
       settle_acc(st.o[db][mb]);
     }
-  }
 }
 
-// One pipeline step.  sc holds S^T of the current tile (complete), sn receives S^T of the next tile and
-// is moved into sc during the last eight MFMAs, when the VALU has nothing else to do (the step body
-// exists once in the program, so the two buffers cannot simply trade names).  On a wavefront's last
-// tile the next S^T is computed from whatever the next stage holds and never looked at.
+// HBM -> LDS loads of one step: the wavefront's share (4 x 1 KiB each) of one K tile and one V tile.
+// kvo/vvo are the per-lane byte offsets inside the tile (row * stride + swizzled chunk), kept across
+// steps because they only change with the tile's row count or stride.
+struct TileLoads {
+  const char* gk;
+  const char* gv;
+  uint32_t lds_k, lds_v;  // LDS byte address of this wavefront's first 1 KiB block in the target stages
+  uint32_t kvo[4], vvo[4];
+};
+
+// One wavefront moves 1 KiB HBM -> LDS, lane l landing at lds_addr + 16 l.  Issued from inline assembly
+// on purpose: the compiler then keeps no account of it and inserts no vmcnt(0) of its own in front of
+// later LDS reads; completion is awaited explicitly with wait_vmcnt<N>().
+__device__ __forceinline__ void dma16(const char* gbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(gbase)
+      : "memory", "m0");
+}
+template <int I>
+__device__ __forceinline__ void issue_one(const TileLoads& ld) {
+  if constexpr (I < 4) dma16(ld.gk, ld.kvo[I], ld.lds_k + I * 4096);
+  else dma16(ld.gv, ld.vvo[I - 4], ld.lds_v + (I - 4) * 4096);
+}
+// Per-lane offsets of the wavefront's four blocks of a tile with cnt rows: block b is rows
+// 16 b + 4 wave + lane / 16, lane l fetching the chunk that the swizzle assigns to slot l % 16.
+// Rows past the end of a ragged tile re-read the last valid row; their scores are masked.
+template <bool IS_V>
+__device__ __forceinline__ void lane_offsets(uint32_t (&vo)[4], int wave, int lane, int cnt, uint32_t stride) {
+  const int row0 = wave * 4 + (lane >> 4);
+  const int slot = lane & 15;
+  const int chunk = IS_V ? (slot ^ ((row0 & 3) << 2)) : (slot ^ (row0 & 15));
+#pragma unroll
+  for (int b = 0; b < 4; ++b) vo[b] = (uint32_t)min(row0 + 16 * b, cnt - 1) * stride + chunk * 16;
+}
+
+// ---- pipelined step ----------------------------------------------------------------------------------
 //   MFMA  0..31  S^T(next): depth step i/4, key block (i/2)%2, row block i%2
-//   MFMA 32..63  PV(current): key step j = (i-32)/8, depth block ((i-32)/2)%4, row block i%2
-// Softmax elements are processed in the order PV consumes them, group g = (j, mb) of 8 elements:
-// one element after each of MFMAs 0..47, two after each of 48..55, so that group (j, mb) is packed
-// to bf16 before MFMA 32 + 8j starts.
-struct Step {
-  const char* k_next;
-  const char* v_cur;
+//   MFMA 32..63  PV(prev):  key step j = (i-32)/8, depth block ((i-32)/2)%4, row block i%2
+// VALU work of the current tile goes in pairs of elements (one bf16 register of P): pair q is
+// exponentiated during slots 2q and 2q+1 and packed at the start of slot 2q+2.
+struct FastStep {
+  const char* k_lds;  // K tile t+1
+  const char* v_lds;  // V tile t-1
   const bf16x8 (&qf)[MB][8];
   f32x16 (&sc)[2][MB];
   f32x16 (&sn)[2][MB];
+  const u32x4 (&pp)[MB][4];
+  u32x4 (&pc)[MB][4];
   WaveState& st;
+  const TileLoads& ld;
   float c;
   uint32_t koff, voff;
-  float ms[MB], rs[MB];
-  bf16x8 pf[MB][4];
+  float ms[MB];
+  float mxn[MB];
+  float pe[2][2];
   bf16x8 kf[2][2];  // [depth-step parity][key block]
-  bf16x8 vf[2];     // [parity of the (j, db) pair]
+  bf16x8 vf[4];     // ring over the (j, db) pairs
 
-  // softmax element E (0..63), in the order PV consumes them
-  template <int E>
-  __device__ __forceinline__ void element() {
-    constexpr int grp = E >> 3, t = E & 7;
+  template <int Q, int HALF>
+  __device__ __forceinline__ void expo() {
+    constexpr int grp = Q >> 2, w = Q & 3;
     constexpr int mb = grp & 1, j = grp >> 1;
-    constexpr int kb = j >> 1, r = 8 * (j & 1) + t;
-    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb][mb][r], c, -ms[mb]));
-    rs[mb] += p;
-    pf[mb][j][t] = (__bf16)p;
+    constexpr int kb = j >> 1, r = 8 * (j & 1) + 2 * w + HALF;
+    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb][mb][r], c, -ms[mb]));
+    pin(p);
+    pe[Q & 1][HALF] = p;
+  }
+  template <int Q>
+  __device__ __forceinline__ void pack() {
+    constexpr int grp = Q >> 2, w = Q & 3;
+    constexpr int mb = grp & 1, j = grp >> 1;
+    uint32_t word = pack_add(pe[Q & 1][0], pe[Q & 1][1], st.l[mb]);
+    pin(word);
+    pin(st.l[mb]);
+    pc[mb][j][w] = word;
+  }
+  // row maxima of the next tile: op Z of 32 chained max3 (Z % 2 = row block), then the half-wave exchange
+  template <int Z>
+  __device__ __forceinline__ void maxop() {
+    if constexpr (Z < 32) {
+      constexpr int mb = Z & 1, k = Z >> 1;
+      if constexpr (k == 0) mxn[mb] = max3(sn[0][mb][0], sn[1][mb][0], sn[1][mb][0]);
+      else mxn[mb] = max3(mxn[mb], sn[0][mb][k], sn[1][mb][k]);
+    } else {
+      mxn[Z - 32] = max_halves(mxn[Z - 32]);
+    }
+  }
+  static constexpr int MAX_FIRST = 36;  // first slot with row-maximum work (S^T(next) is complete and settled)
+  static constexpr int zslot(int z) { return MAX_FIRST + z * (64 - MAX_FIRST) / 34; }
+
+  template <int I, int... Zs>
+  __device__ __forceinline__ void run_max(std::integer_sequence<int, Zs...>) {
+    ((zslot(Zs) == I ? maxop<Zs>() : (void)0), ...);
   }
 
-  // MFMA slot I (0..63) with the VALU work that rides along
   template <int I>
   __device__ __forceinline__ void slot() {
     if constexpr (I < 32) {
       constexpr int ks = I >> 2, kb = (I >> 1) & 1, mb = I & 1;
       if constexpr ((I & 3) == 0 && ks + 1 < 8) {
-        kf[(ks + 1) & 1][0] = read_k_frag(k_next, koff, 0, ks + 1);
-        kf[(ks + 1) & 1][1] = read_k_frag(k_next, koff, 1, ks + 1);
+        kf[(ks + 1) & 1][0] = read_k_frag(k_lds, koff, 0, ks + 1);
+        kf[(ks + 1) & 1][1] = read_k_frag(k_lds, koff, 1, ks + 1);
       }
       if constexpr (ks == 0) mfma_s_first(sn[kb][mb], kf[0][kb], qf[mb][0]);
       else mfma_s(sn[kb][mb], kf[ks & 1][kb], qf[mb][ks]);
-      if constexpr (I == 28) vf[0] = read_v_frag(v_cur, voff, 0, 0);
+      if constexpr (I >= 26 && (I & 1) == 0) vf[(I - 26) >> 1] = read_v_frag(v_lds, voff, 0, (I - 26) >> 1);
     } else {
       constexpr int pair = (I - 32) >> 1, mb = I & 1;  // pair = j * 4 + db
       constexpr int j = pair >> 2, db = pair & 3;
-      if constexpr (mb == 0 && pair + 1 < 16)
-        vf[(pair + 1) & 1] = read_v_frag(v_cur, voff, (pair + 1) >> 2, (pair + 1) & 3);
-      mfma_o(st.o[db][mb], vf[pair & 1], pf[mb][j]);
+      if constexpr (mb == 0 && pair + 3 < 16)
+        vf[(pair + 3) & 3] = read_v_frag(v_lds, voff, (pair + 3) >> 2, (pair + 3) & 3);
+      mfma_o(st.o[db][mb], vf[pair & 3], pp[mb][j]);
     }
-    if constexpr (I < 48) {
-      element<I>();
-    } else if constexpr (I < 56) {
-      element<48 + 2 * (I - 48)>();
-      element<48 + 2 * (I - 48) + 1>();
+    // softmax of the current tile
+    constexpr int q = I >> 1;
+    if constexpr ((I & 1) == 0) {
+      if constexpr (q > 0) pack<q - 1>();
+      expo<q, 0>();
     } else {
-      // 8 of the 64 registers of the next S^T per slot: [kb][mb] block (I-56)/2, half (I-56)%2
-      constexpr int blk = (I - 56) >> 1, half = (I - 56) & 1;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) sc[blk >> 1][blk & 1][8 * half + r] = sn[blk >> 1][blk & 1][8 * half + r];
+      expo<q, 1>();
     }
+    // HBM -> LDS loads of later tiles
+    if constexpr ((I & 1) == 1 && I < 16) issue_one<(I - 1) / 2>(ld);
+    // row maxima of the next tile
+    if constexpr (I >= MAX_FIRST) run_max<I>(std::make_integer_sequence<int, 34>{});
     __builtin_amdgcn_sched_barrier(0);
   }
 
@@ -202,24 +304,25 @@ struct Step {
   }
 };
 
-__device__ __forceinline__ void tile_step(const char* k_next, const char* v_cur, const bf16x8 (&qf)[MB][8],
-                                          f32x16 (&sc)[2][MB], f32x16 (&sn)[2][MB], WaveState& st,
-                                          const int (&limit)[MB], float c, int lane, int cnt, int pos,
-                                          bool need_mask, uint32_t koff, uint32_t voff) {
-  Step s{k_next, v_cur, qf, sc, sn, st, c, koff, voff};
-  s.kf[0][0] = read_k_frag(k_next, koff, 0, 0);
-  s.kf[0][1] = read_k_frag(k_next, koff, 1, 0);
-  if (need_mask) mask_tile(sc, limit, lane, cnt, pos);
-  update_reference(sc, st, c);
+// S^T of one tile, nothing overlapped.
+__device__ __forceinline__ void plain_s(const char* k_lds, const bf16x8 (&qf)[MB][8], f32x16 (&s)[2][MB],
+                                        uint32_t koff) {
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    s.ms[mb] = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
-    s.rs[mb] = 0.f;
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 a0 = read_k_frag(k_lds, koff, 0, ks);
+    const bf16x8 a1 = read_k_frag(k_lds, koff, 1, ks);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      if (ks == 0) {
+        mfma_s_first(s[0][mb], a0, qf[mb][0]);
+        mfma_s_first(s[1][mb], a1, qf[mb][0]);
+      } else {
+        mfma_s(s[0][mb], a0, qf[mb][ks]);
+        mfma_s(s[1][mb], a1, qf[mb][ks]);
+      }
+    }
   }
-  __builtin_amdgcn_sched_barrier(0);
-  s.run(std::make_integer_sequence<int, 64>{});
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) st.l[mb] += s.rs[mb];
+  settle(s[0][0], s[0][1], s[1][0], s[1][1]);
 }
 
 __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
@@ -259,75 +362,192 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   }
   const uint32_t koff = k_lane_off(lane), voff = v_lane_off(lane);
 
-  // LDS ring of 4 stages; tile t lives in stage t % 4.  Step t needs V of tile t and K of tile t+1,
-  // so before step t every wavefront waits for its own share of tile t+1, then the barrier makes the
-  // whole tile visible and proves that step t-1 is finished everywhere, which frees stage (t+3) % 4
-  // for the loads of tile t+3.
-  KvCursor cur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
-  auto issue = [&](const KvTile& t, int stage) {
-    char* kl = smem + stage * TILE_STAGE_BYTES;
-    char* vl = kl + TILE_KT * ROW_BYTES;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      load_rows4<false>(t.k, t.stride, t.cnt, kl, wave + 4 * b, lane);
-      load_rows4<true>(t.v, t.stride, t.cnt, vl, wave + 4 * b, lane);
+  // Two LDS rings of three 16 KiB stages: K tile u and V tile u live in stage u % 3 of their ring.
+  // Step t reads K(t+1) and V(t-1) and loads K(t+3) and V(t+1), i.e. every tile is requested two steps
+  // before its first use.  The barrier at the top of step t proves step t-1 is finished everywhere,
+  // which is what frees the stages of K(t) and V(t-2) for those loads.  Past the end of the key range
+  // the last tile is simply loaded again (into stages nobody reads any more), so that every step
+  // leaves exactly eight loads per wavefront in flight and one wait count fits all steps.
+  char* const k_ring = smem;
+  char* const v_ring = smem + TILE_RING * TILE_STAGE_BYTES;
+  KvCursor kcur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
+  KvCursor vcur = kcur;
+  KvTile tk, tv;  // next K tile / V tile to load
+  TileLoads ld;
+  int k_cnt = -1, v_cnt = -1;
+  uint32_t k_stride = 0, v_stride = 0;
+  auto aim_k = [&](int stage) {
+    if (tk.cnt != k_cnt || tk.stride != k_stride) {
+      k_cnt = tk.cnt;
+      k_stride = tk.stride;
+      lane_offsets<false>(ld.kvo, wave, lane, k_cnt, k_stride);
     }
+    ld.gk = tk.k;
+    ld.lds_k = (uint32_t)(uintptr_t)(lds_void_ptr)(k_ring + stage * TILE_STAGE_BYTES + wave * 1024);
   };
-  // (cnt, pos) of the tile being computed and of the two after it; pos < 0 marks "no such tile"
-  int cnt0 = 0, pos0 = -1, cnt1 = 0, pos1 = -1, cnt2 = 0, pos2 = -1;
-  {
-    KvTile t;
-    if (cur.next(c, g, TILE_KT, t)) { issue(t, 0); cnt0 = t.cnt; pos0 = t.pos; }
-    if (pos0 >= 0 && cur.next(c, g, TILE_KT, t)) { issue(t, 1); cnt1 = t.cnt; pos1 = t.pos; }
-    if (pos1 >= 0 && cur.next(c, g, TILE_KT, t)) { issue(t, 2); cnt2 = t.cnt; pos2 = t.pos; }
-  }
-  f32x16 sa[2][MB], sb[2][MB];
+  auto aim_v = [&](int stage) {
+    if (tv.cnt != v_cnt || tv.stride != v_stride) {
+      v_cnt = tv.cnt;
+      v_stride = tv.stride;
+      lane_offsets<true>(ld.vvo, wave, lane, v_cnt, v_stride);
+    }
+    ld.gv = tv.v;
+    ld.lds_v = (uint32_t)(uintptr_t)(lds_void_ptr)(v_ring + stage * TILE_STAGE_BYTES + wave * 1024);
+  };
+  auto issue_k = [&]() {
+    issue_one<0>(ld);
+    issue_one<1>(ld);
+    issue_one<2>(ld);
+    issue_one<3>(ld);
+  };
+  auto issue_v = [&]() {
+    issue_one<4>(ld);
+    issue_one<5>(ld);
+    issue_one<6>(ld);
+    issue_one<7>(ld);
+  };
 
-  // prologue: S^T of tile 0
-  if (pos2 >= 0) wait_vmcnt<16>(); else if (pos1 >= 0) wait_vmcnt<8>(); else wait_vmcnt<0>();
-  __builtin_amdgcn_s_barrier();
-  if (pos0 >= 0 && pos0 <= wave_max_limit) {
-    const char* kl = smem;
+  if (!kcur.next(c, g, TILE_KT, tk)) return;  // empty key range: the planner never produces one
+  aim_k(0);
+  issue_k();
+  (void)kcur.next(c, g, TILE_KT, tk);  // when the range ends the old tile stays in tk
+  aim_k(1);
+  issue_k();
+  (void)kcur.next(c, g, TILE_KT, tk);
+
+  f32x16 sa[2][MB], sb[2][MB];
+  u32x4 pa[MB][4], pb[MB][4];
+  // Step 0 applies P(-1) = 0 to "V(-1)", stage 2 of the V ring: zero-fill it so that no stale NaN
+  // pattern meets those zeros.  (Every stage of the K ring is loaded before it is read.)
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a0 = read_k_frag(kl, koff, 0, ks);
-      const bf16x8 a1 = read_k_frag(kl, koff, 1, ks);
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pb[mb][j] = u32x4{0, 0, 0, 0};
+  {
+    u32x4* z = (u32x4*)(v_ring + 2 * TILE_STAGE_BYTES);
+#pragma unroll
+    for (int i = 0; i < TILE_STAGE_BYTES / (256 * 16); ++i) z[i * 256 + threadIdx.x] = u32x4{0, 0, 0, 0};
+  }
+
+  // tile t ("current") of the step about to run and tile t+1 ("next"); cnt 0 = no such tile
+  bool ex_n = vcur.next(c, g, TILE_KT, tv);
+  int cnt_c = 0, pos_c = 0, cnt_n = tv.cnt, pos_n = tv.pos;
+  bool ex_c = false;
+  bool mx_valid = false, pending = false;
+  float mx[MB] = {0.f, 0.f}, alpha[MB] = {1.f, 1.f};
+
+  // step -1: S^T(0)
+  wait_vmcnt<4>();
+  __builtin_amdgcn_s_barrier();
+  aim_k(2);
+  aim_v(0);
+  issue_k();
+  issue_v();
+  plain_s(k_ring, qf, sa, koff);
+
+  int stage = 0;  // t % 3
+#ifdef DK_PROF
+  long long pacc[6] = {0, 0, 0, 0, 0, 0};
+  const long long pstart = __builtin_readcyclecounter();
+  const long long wstart = wall_clock64();
+#endif
+
+  auto step = [&](f32x16(&sc)[2][MB], f32x16(&sn)[2][MB], u32x4(&pp)[MB][4], u32x4(&pc)[MB][4])
+                  __attribute__((always_inline)) {
+    DK_PROF_T(t0);
+    wait_vmcnt<8>();
+    __builtin_amdgcn_s_barrier();
+    DK_PROF_T(t1);
+    const int s1 = stage == 2 ? 0 : stage + 1, s2 = stage == 0 ? 2 : stage - 1;
+    const char* k_lds = k_ring + s1 * TILE_STAGE_BYTES;  // K(t+1)
+    const char* v_lds = v_ring + s2 * TILE_STAGE_BYTES;  // V(t-1)
+    aim_k(stage);                                        // K(t+3)
+    aim_v(s1);                                           // V(t+1)
+    if (pending) {  // O still carries the reference maxima of two steps ago
+      rescale_o(st, alpha);
+      pending = false;
+    }
+    // a tile that does not exist or lies beyond the wavefront's rows counts as having no valid key
+    const int cnt_eff = (ex_c && pos_c <= wave_max_limit) ? cnt_c : 0;
+    if (cnt_eff < TILE_KT || pos_c + TILE_KT - 1 > wave_min_limit) {
+      mask_tile(sc, limit, lane, cnt_eff, pos_c);
+      mx_valid = false;
+    }
+    if (!mx_valid) row_max(sc, mx);
+    bool grow = false;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) grow |= mx[mb] * c.c > st.m[mb] + RESCALE_SLACK;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        if (ks == 0) {
-          mfma_s_first(sa[0][mb], a0, qf[mb][0]);
-          mfma_s_first(sa[1][mb], a1, qf[mb][0]);
-        } else {
-          mfma_s(sa[0][mb], a0, qf[mb][ks]);
-          mfma_s(sa[1][mb], a1, qf[mb][ks]);
-        }
+        const float mn = fmaxf(st.m[mb], mx[mb] * c.c);
+        const float mz = (mn == -INFINITY) ? 0.f : mn;
+        alpha[mb] = __builtin_amdgcn_exp2f(st.m[mb] - mz);  // 1 for rows whose maximum did not move
+        st.m[mb] = mn;
+        st.l[mb] *= alpha[mb];
       }
+      pending = true;
     }
-    settle(sa[0][0], sa[0][1], sa[1][0], sa[1][1]);
-  }
-
-  int stage = 0;  // stage of the tile being computed
-  while (pos0 >= 0) {
-    // tile t+1 must have landed (tile t+2 may still be in flight)
-    if (pos2 >= 0) wait_vmcnt<8>(); else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    int cnt3 = 0, pos3 = -1;
+    DK_PROF_T(t2);
     {
-      KvTile t;
-      if (pos2 >= 0 && cur.next(c, g, TILE_KT, t)) { issue(t, (stage + 3) & 3); cnt3 = t.cnt; pos3 = t.pos; }
+      FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, c.c, koff, voff};
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) f.ms[mb] = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
+      f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
+      f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      f.run(std::make_integer_sequence<int, 64>{});
+      f.pack<31>();
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) mx[mb] = f.mxn[mb];
+      mx_valid = true;
     }
-    if (pos0 <= wave_max_limit) {
-      const char* vl = smem + stage * TILE_STAGE_BYTES + TILE_KT * ROW_BYTES;
-      const char* kn = smem + ((stage + 1) & 3) * TILE_STAGE_BYTES;
-      const bool need_mask = cnt0 < TILE_KT || pos0 + TILE_KT - 1 > wave_min_limit;
-      tile_step(kn, vl, qf, sa, sb, st, limit, c.c, lane, cnt0, pos0, need_mask, koff, voff);
-    }
-    cnt0 = cnt1; pos0 = pos1;
-    cnt1 = cnt2; pos1 = pos2;
-    cnt2 = cnt3; pos2 = pos3;
-    stage = (stage + 1) & 3;
-  }
+    DK_PROF_T(t3);
+    DK_PROF_ADD(0, t1 - t0);
+    DK_PROF_ADD(1, t2 - t1);
+    DK_PROF_ADD(2, t3 - t2);
+    DK_PROF_ADD(3, 1);
+    // on to step t+1
+    ex_c = ex_n;
+    cnt_c = cnt_n;
+    pos_c = pos_n;
+    (void)kcur.next(c, g, TILE_KT, tk);
+    ex_n = vcur.next(c, g, TILE_KT, tv);
+    cnt_n = tv.cnt;
+    pos_n = tv.pos;
+    stage = s1;
+  };
 
+  // entering step 0
+  ex_c = ex_n;
+  cnt_c = cnt_n;
+  pos_c = pos_n;
+  (void)kcur.next(c, g, TILE_KT, tk);
+  ex_n = vcur.next(c, g, TILE_KT, tv);
+  cnt_n = tv.cnt;
+  pos_n = tv.pos;
+  // steps 0 .. T for T tiles: the last one only applies P(T-1)
+  while (true) {
+    bool last = !ex_c;
+    step(sa, sb, pb, pa);
+    if (last) break;
+    last = !ex_c;
+    step(sb, sa, pa, pb);
+    if (last) break;
+  }
+  if (pending) rescale_o(st, alpha);
+  wait_vmcnt<0>();
+
+#ifdef DK_PROF
+  if (lane == 0) {
+    atomicAdd(&g_prof[0], (unsigned long long)(__builtin_readcyclecounter() - pstart));
+    atomicAdd(&g_prof[1], (unsigned long long)pacc[0]);
+    atomicAdd(&g_prof[2], (unsigned long long)pacc[1]);
+    atomicAdd(&g_prof[3], (unsigned long long)pacc[2]);
+    atomicAdd(&g_prof[4], (unsigned long long)pacc[3]);
+    atomicAdd(&g_prof[6], (unsigned long long)(wall_clock64() - wstart));
+  }
+#endif
   if (wave_active) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
