@@ -46,9 +46,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int TILE_KT = 64;
-constexpr int TILE_RING = 3;                           // stages per ring, K and V each
+constexpr int TILE_K_RING = 3, TILE_V_RING = 5;        // stages per ring
 constexpr int TILE_STAGE_BYTES = TILE_KT * ROW_BYTES;  // 16 KiB
-constexpr int TILE_LDS_BYTES = 2 * TILE_RING * TILE_STAGE_BYTES;
+constexpr int TILE_LDS_BYTES = (TILE_K_RING + TILE_V_RING) * TILE_STAGE_BYTES;
 constexpr int MB = 2;  // 32-row blocks per wavefront
 
 // S^T accumulators live in VGPRs, O^T accumulators and Q in AGPRs.
@@ -77,9 +77,11 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 }
 // Keeps a value's computation where the source has it: ordinary arithmetic whose only consumers are
 // in a later step would otherwise be sunk out of the MFMA schedule it is meant to fill.
+// (Input-only on purpose: an asm that redefined the register would make the hazard recogniser pad its
+// next use with a wait state.)
 template <typename T>
-__device__ __forceinline__ void pin(T& x) {
-  asm volatile("" : "+v"(x));
+__device__ __forceinline__ void pin(const T& x) {
+  asm volatile("" : : "v"(x));
 }
 // max over the two half-waves: lane l and lane l ^ 32 both get max(x[l], x[l ^ 32])
 __device__ __forceinline__ float max_halves(float x) {
@@ -209,7 +211,10 @@ __device__ __forceinline__ void lane_offsets(uint32_t (&vo)[4], int wave, int la
 //   MFMA  0..31  S^T(next): depth step i/4, key block (i/2)%2, row block i%2
 //   MFMA 32..63  PV(prev):  key step j = (i-32)/8, depth block ((i-32)/2)%4, row block i%2
 // VALU work of the current tile goes in pairs of elements (one bf16 register of P): pair q is
-// exponentiated during slots 2q and 2q+1 and packed at the start of slot 2q+2.
+// exponentiated during slots 2q and 2q+1 and packed in slot 2q+2, after that slot's first multiply-add
+// (so that the pack never directly follows the v_exp_f32 whose result it reads).
+// LDS reads: K fragments one depth step ahead; V fragments two (j, db) pairs at a time, four slots
+// ahead of their first use.  Each group is awaited once, at its first use.
 struct FastStep {
   const char* k_lds;  // K tile t+1
   const char* v_lds;  // V tile t-1
@@ -220,20 +225,25 @@ struct FastStep {
   u32x4 (&pc)[MB][4];
   WaveState& st;
   const TileLoads& ld;
+  const float (&ms)[MB];
   float c;
   uint32_t koff, voff;
-  float ms[MB];
   float mxn[MB];
-  float pe[2][2];
+  float xe;         // scaled score waiting for its exp2
+  float pe[2][2];   // [pair parity][element]
   bf16x8 kf[2][2];  // [depth-step parity][key block]
   bf16x8 vf[4];     // ring over the (j, db) pairs
 
   template <int Q, int HALF>
-  __device__ __forceinline__ void expo() {
+  __device__ __forceinline__ void scale() {
     constexpr int grp = Q >> 2, w = Q & 3;
     constexpr int mb = grp & 1, j = grp >> 1;
     constexpr int kb = j >> 1, r = 8 * (j & 1) + 2 * w + HALF;
-    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb][mb][r], c, -ms[mb]));
+    xe = __builtin_fmaf(sc[kb][mb][r], c, -ms[mb]);
+  }
+  template <int Q, int HALF>
+  __device__ __forceinline__ void expo() {
+    float p = __builtin_amdgcn_exp2f(xe);
     pin(p);
     pe[Q & 1][HALF] = p;
   }
@@ -264,31 +274,49 @@ struct FastStep {
   __device__ __forceinline__ void run_max(std::integer_sequence<int, Zs...>) {
     ((zslot(Zs) == I ? maxop<Zs>() : (void)0), ...);
   }
+  template <int PAIR>
+  __device__ __forceinline__ void read_v_pair() {
+    vf[PAIR & 3] = read_v_frag(v_lds, voff, PAIR >> 2, PAIR & 3);
+  }
 
   template <int I>
   __device__ __forceinline__ void slot() {
     if constexpr (I < 32) {
       constexpr int ks = I >> 2, kb = (I >> 1) & 1, mb = I & 1;
-      if constexpr ((I & 3) == 0 && ks + 1 < 8) {
-        kf[(ks + 1) & 1][0] = read_k_frag(k_lds, koff, 0, ks + 1);
-        kf[(ks + 1) & 1][1] = read_k_frag(k_lds, koff, 1, ks + 1);
+      if constexpr ((I & 3) == 0) {
+        if constexpr (ks + 1 < 8) {
+          kf[(ks + 1) & 1][0] = read_k_frag(k_lds, koff, 0, ks + 1);
+          kf[(ks + 1) & 1][1] = read_k_frag(k_lds, koff, 1, ks + 1);
+        }
+        // one wait for both key blocks of this depth step
+        asm volatile("" : : "a"(kf[ks & 1][0]), "a"(kf[ks & 1][1]));
       }
       if constexpr (ks == 0) mfma_s_first(sn[kb][mb], kf[0][kb], qf[mb][0]);
       else mfma_s(sn[kb][mb], kf[ks & 1][kb], qf[mb][ks]);
-      if constexpr (I >= 26 && (I & 1) == 0) vf[(I - 26) >> 1] = read_v_frag(v_lds, voff, 0, (I - 26) >> 1);
+      if constexpr (I == 28) {
+        read_v_pair<0>();
+        read_v_pair<1>();
+      }
     } else {
       constexpr int pair = (I - 32) >> 1, mb = I & 1;  // pair = j * 4 + db
       constexpr int j = pair >> 2, db = pair & 3;
-      if constexpr (mb == 0 && pair + 3 < 16)
-        vf[(pair + 3) & 3] = read_v_frag(v_lds, voff, (pair + 3) >> 2, (pair + 3) & 3);
+      if constexpr (((I - 32) & 3) == 0) {
+        if constexpr (pair + 2 < 16) {
+          read_v_pair<pair + 2>();
+          read_v_pair<pair + 3>();
+        }
+        asm volatile("" : : "a"(vf[pair & 3]), "a"(vf[(pair + 1) & 3]));
+      }
       mfma_o(st.o[db][mb], vf[pair & 3], pp[mb][j]);
     }
     // softmax of the current tile
     constexpr int q = I >> 1;
     if constexpr ((I & 1) == 0) {
-      if constexpr (q > 0) pack<q - 1>();
+      scale<q, 0>();
       expo<q, 0>();
+      if constexpr (q > 0) pack<q - 1>();
     } else {
+      scale<q, 1>();
       expo<q, 1>();
     }
     // HBM -> LDS loads of later tiles
@@ -362,90 +390,104 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   }
   const uint32_t koff = k_lane_off(lane), voff = v_lane_off(lane);
 
-  // Two LDS rings of three 16 KiB stages: K tile u and V tile u live in stage u % 3 of their ring.
-  // Step t reads K(t+1) and V(t-1) and loads K(t+3) and V(t+1), i.e. every tile is requested two steps
-  // before its first use.  The barrier at the top of step t proves step t-1 is finished everywhere,
-  // which is what frees the stages of K(t) and V(t-2) for those loads.  Past the end of the key range
-  // the last tile is simply loaded again (into stages nobody reads any more), so that every step
-  // leaves exactly eight loads per wavefront in flight and one wait count fits all steps.
+  // Two LDS rings of 16 KiB stages: K tile u lives in stage u % 3 of the K ring, V tile u in stage
+  // u % 5 of the V ring.  Step t reads K(t+1) and V(t-1) and requests tile t+3 (K and V), i.e. every
+  // tile is requested two steps before its first use.  The barrier at the top of step t proves step
+  // t-1 is finished everywhere, which is what frees the stages of K(t) and V(t-2) for those loads.
+  // Past the end of the key range the last tile is simply loaded again (into stages nobody reads any
+  // more), so that every step leaves exactly eight loads per wavefront in flight and one wait count
+  // fits all steps.
   char* const k_ring = smem;
-  char* const v_ring = smem + TILE_RING * TILE_STAGE_BYTES;
-  KvCursor kcur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
-  KvCursor vcur = kcur;
-  KvTile tk, tv;  // next K tile / V tile to load
+  char* const v_ring = smem + TILE_K_RING * TILE_STAGE_BYTES;
+  const uint32_t k_ring_lds = (uint32_t)(uintptr_t)(lds_void_ptr)k_ring + wave * 1024;
+  const uint32_t v_ring_lds = (uint32_t)(uintptr_t)(lds_void_ptr)v_ring + wave * 1024;
+  KvCursor cur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
+  KvTile tl;  // next tile to load
   TileLoads ld;
-  int k_cnt = -1, v_cnt = -1;
-  uint32_t k_stride = 0, v_stride = 0;
-  auto aim_k = [&](int stage) {
-    if (tk.cnt != k_cnt || tk.stride != k_stride) {
-      k_cnt = tk.cnt;
-      k_stride = tk.stride;
-      lane_offsets<false>(ld.kvo, wave, lane, k_cnt, k_stride);
-    }
-    ld.gk = tk.k;
-    ld.lds_k = (uint32_t)(uintptr_t)(lds_void_ptr)(k_ring + stage * TILE_STAGE_BYTES + wave * 1024);
+  int ld_cnt = -1;
+  uint32_t ld_stride = 0;
+  auto offsets_stale = [&]() { return tl.cnt != ld_cnt || tl.stride != ld_stride; };
+  auto refresh_offsets = [&]() {
+    ld_cnt = tl.cnt;
+    ld_stride = tl.stride;
+    lane_offsets<false>(ld.kvo, wave, lane, ld_cnt, ld_stride);
+    lane_offsets<true>(ld.vvo, wave, lane, ld_cnt, ld_stride);
   };
-  auto aim_v = [&](int stage) {
-    if (tv.cnt != v_cnt || tv.stride != v_stride) {
-      v_cnt = tv.cnt;
-      v_stride = tv.stride;
-      lane_offsets<true>(ld.vvo, wave, lane, v_cnt, v_stride);
-    }
-    ld.gv = tv.v;
-    ld.lds_v = (uint32_t)(uintptr_t)(lds_void_ptr)(v_ring + stage * TILE_STAGE_BYTES + wave * 1024);
+  auto aim = [&](int k_stage, int v_stage) {
+    ld.gk = tl.k;
+    ld.gv = tl.v;
+    ld.lds_k = k_ring_lds + k_stage * TILE_STAGE_BYTES;
+    ld.lds_v = v_ring_lds + v_stage * TILE_STAGE_BYTES;
   };
-  auto issue_k = [&]() {
+  auto issue_all = [&]() {
     issue_one<0>(ld);
     issue_one<1>(ld);
     issue_one<2>(ld);
     issue_one<3>(ld);
-  };
-  auto issue_v = [&]() {
     issue_one<4>(ld);
     issue_one<5>(ld);
     issue_one<6>(ld);
     issue_one<7>(ld);
   };
 
-  if (!kcur.next(c, g, TILE_KT, tk)) return;  // empty key range: the planner never produces one
-  aim_k(0);
-  issue_k();
-  (void)kcur.next(c, g, TILE_KT, tk);  // when the range ends the old tile stays in tk
-  aim_k(1);
-  issue_k();
-  (void)kcur.next(c, g, TILE_KT, tk);
+  // (cnt, pos) of tiles t .. t+2 of the step about to run; cnt 0 = no such tile
+  int cnt0 = 0, pos0 = 0, cnt1 = 0, pos1 = 0, cnt2 = 0, pos2 = 0;
+  if (!cur.next(c, g, TILE_KT, tl)) return;  // empty key range: the planner never produces one
+  cnt1 = tl.cnt;  // becomes tile 0 when step -1 hands over to step 0
+  pos1 = tl.pos;
+  refresh_offsets();
+  aim(0, 0);
+  issue_all();
+  if (cur.next(c, g, TILE_KT, tl)) {  // when the range ends the old tile stays in tl
+    cnt2 = tl.cnt;
+    pos2 = tl.pos;
+  }
+  if (offsets_stale()) refresh_offsets();
+  aim(1, 1);
+  issue_all();
 
   f32x16 sa[2][MB], sb[2][MB];
   u32x4 pa[MB][4], pb[MB][4];
-  // Step 0 applies P(-1) = 0 to "V(-1)", stage 2 of the V ring: zero-fill it so that no stale NaN
+  // Step 0 applies P(-1) = 0 to "V(-1)", stage 4 of the V ring: zero-fill it so that no stale NaN
   // pattern meets those zeros.  (Every stage of the K ring is loaded before it is read.)
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int j = 0; j < 4; ++j) pb[mb][j] = u32x4{0, 0, 0, 0};
   {
-    u32x4* z = (u32x4*)(v_ring + 2 * TILE_STAGE_BYTES);
+    u32x4* z = (u32x4*)(v_ring + 4 * TILE_STAGE_BYTES);
 #pragma unroll
     for (int i = 0; i < TILE_STAGE_BYTES / (256 * 16); ++i) z[i * 256 + threadIdx.x] = u32x4{0, 0, 0, 0};
   }
 
-  // tile t ("current") of the step about to run and tile t+1 ("next"); cnt 0 = no such tile
-  bool ex_n = vcur.next(c, g, TILE_KT, tv);
-  int cnt_c = 0, pos_c = 0, cnt_n = tv.cnt, pos_n = tv.pos;
-  bool ex_c = false;
   bool mx_valid = false, pending = false;
   float mx[MB] = {0.f, 0.f}, alpha[MB] = {1.f, 1.f};
+  float ms[MB] = {0.f, 0.f};  // the reference maxima as subtracted from the scores: m, or 0 while m = -inf
+  float gval = 0.f;           // how far the tile's scores outgrow the reference maxima (log2 units)
 
-  // step -1: S^T(0)
-  wait_vmcnt<4>();
+  // step -1: S^T(0); requests tile 2
+  int cnt3 = 0, pos3 = 0;
+  auto fetch = [&]() {
+    cnt3 = 0;
+    if (cur.next(c, g, TILE_KT, tl)) {
+      cnt3 = tl.cnt;
+      pos3 = tl.pos;
+    }
+  };
+  fetch();
+  wait_vmcnt<8>();
   __builtin_amdgcn_s_barrier();
-  aim_k(2);
-  aim_v(0);
-  issue_k();
-  issue_v();
+  if (offsets_stale()) refresh_offsets();
+  aim(2, 2);
+  issue_all();
   plain_s(k_ring, qf, sa, koff);
+  cnt0 = cnt1; pos0 = pos1;
+  cnt1 = cnt2; pos1 = pos2;
+  cnt2 = cnt3; pos2 = pos3;
+  fetch();
 
-  int stage = 0;  // t % 3
+  // byte offsets of the stages step t uses: K(t+1) read, K(t+3) written; V(t-1) read, V(t+3) written
+  int k_rd = 1 * TILE_STAGE_BYTES, k_wr = 0, v_rd = 4 * TILE_STAGE_BYTES, v_wr = 3 * TILE_STAGE_BYTES;
 #ifdef DK_PROF
   long long pacc[6] = {0, 0, 0, 0, 0, 0};
   const long long pstart = __builtin_readcyclecounter();
@@ -454,45 +496,44 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
 
   auto step = [&](f32x16(&sc)[2][MB], f32x16(&sn)[2][MB], u32x4(&pp)[MB][4], u32x4(&pc)[MB][4])
                   __attribute__((always_inline)) {
-    DK_PROF_T(t0);
     wait_vmcnt<8>();
     __builtin_amdgcn_s_barrier();
     DK_PROF_T(t1);
-    const int s1 = stage == 2 ? 0 : stage + 1, s2 = stage == 0 ? 2 : stage - 1;
-    const char* k_lds = k_ring + s1 * TILE_STAGE_BYTES;  // K(t+1)
-    const char* v_lds = v_ring + s2 * TILE_STAGE_BYTES;  // V(t-1)
-    aim_k(stage);                                        // K(t+3)
-    aim_v(s1);                                           // V(t+1)
-    if (pending) {  // O still carries the reference maxima of two steps ago
-      rescale_o(st, alpha);
-      pending = false;
-    }
+    const char* k_lds = k_ring + k_rd;
+    const char* v_lds = v_ring + v_rd;
+    ld.gk = tl.k;
+    ld.gv = tl.v;
+    ld.lds_k = k_ring_lds + k_wr;
+    ld.lds_v = v_ring_lds + v_wr;
     // a tile that does not exist or lies beyond the wavefront's rows counts as having no valid key
-    const int cnt_eff = (ex_c && pos_c <= wave_max_limit) ? cnt_c : 0;
-    if (cnt_eff < TILE_KT || pos_c + TILE_KT - 1 > wave_min_limit) {
-      mask_tile(sc, limit, lane, cnt_eff, pos_c);
-      mx_valid = false;
+    const int cnt_eff = pos0 <= wave_max_limit ? cnt0 : 0;
+    const bool need_mask = cnt_eff < TILE_KT || pos0 + TILE_KT - 1 > wave_min_limit;
+    if (pending || need_mask || !mx_valid || offsets_stale()) {  // rare, all of it
+      if (offsets_stale()) refresh_offsets();
+      if (pending) {  // O still carries the reference maxima of two steps ago
+        rescale_o(st, alpha);
+        pending = false;
+      }
+      if (need_mask) mask_tile(sc, limit, lane, cnt_eff, pos0);
+      if (need_mask || !mx_valid) {
+        row_max(sc, mx);
+        gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
+      }
     }
-    if (!mx_valid) row_max(sc, mx);
-    bool grow = false;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) grow |= mx[mb] * c.c > st.m[mb] + RESCALE_SLACK;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    if (__builtin_amdgcn_ballot_w64(gval > RESCALE_SLACK) != 0) {
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         const float mn = fmaxf(st.m[mb], mx[mb] * c.c);
         const float mz = (mn == -INFINITY) ? 0.f : mn;
         alpha[mb] = __builtin_amdgcn_exp2f(st.m[mb] - mz);  // 1 for rows whose maximum did not move
         st.m[mb] = mn;
+        ms[mb] = mz;
         st.l[mb] *= alpha[mb];
       }
       pending = true;
     }
-    DK_PROF_T(t2);
     {
-      FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, c.c, koff, voff};
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) f.ms[mb] = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
+      FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, ms, c.c, koff, voff};
       f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
       f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -500,38 +541,30 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
       f.pack<31>();
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) mx[mb] = f.mxn[mb];
+      // -inf - -inf for rows that have seen no key yet: NaN compares false, which is right (nothing to raise)
+      gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
       mx_valid = true;
     }
     DK_PROF_T(t3);
-    DK_PROF_ADD(0, t1 - t0);
-    DK_PROF_ADD(1, t2 - t1);
-    DK_PROF_ADD(2, t3 - t2);
+    DK_PROF_ADD(2, t3 - t1);
     DK_PROF_ADD(3, 1);
     // on to step t+1
-    ex_c = ex_n;
-    cnt_c = cnt_n;
-    pos_c = pos_n;
-    (void)kcur.next(c, g, TILE_KT, tk);
-    ex_n = vcur.next(c, g, TILE_KT, tv);
-    cnt_n = tv.cnt;
-    pos_n = tv.pos;
-    stage = s1;
+    cnt0 = cnt1; pos0 = pos1;
+    cnt1 = cnt2; pos1 = pos2;
+    cnt2 = cnt3; pos2 = pos3;
+    fetch();
+    k_rd = k_rd == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_rd + TILE_STAGE_BYTES;
+    k_wr = k_wr == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_wr + TILE_STAGE_BYTES;
+    v_rd = v_rd == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_rd + TILE_STAGE_BYTES;
+    v_wr = v_wr == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_wr + TILE_STAGE_BYTES;
   };
 
-  // entering step 0
-  ex_c = ex_n;
-  cnt_c = cnt_n;
-  pos_c = pos_n;
-  (void)kcur.next(c, g, TILE_KT, tk);
-  ex_n = vcur.next(c, g, TILE_KT, tv);
-  cnt_n = tv.cnt;
-  pos_n = tv.pos;
   // steps 0 .. T for T tiles: the last one only applies P(T-1)
   while (true) {
-    bool last = !ex_c;
+    bool last = cnt0 == 0;
     step(sa, sb, pb, pa);
     if (last) break;
-    last = !ex_c;
+    last = cnt0 == 0;
     step(sb, sa, pa, pb);
     if (last) break;
   }
@@ -541,8 +574,6 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
 #ifdef DK_PROF
   if (lane == 0) {
     atomicAdd(&g_prof[0], (unsigned long long)(__builtin_readcyclecounter() - pstart));
-    atomicAdd(&g_prof[1], (unsigned long long)pacc[0]);
-    atomicAdd(&g_prof[2], (unsigned long long)pacc[1]);
     atomicAdd(&g_prof[3], (unsigned long long)pacc[2]);
     atomicAdd(&g_prof[4], (unsigned long long)pacc[3]);
     atomicAdd(&g_prof[6], (unsigned long long)(wall_clock64() - wstart));

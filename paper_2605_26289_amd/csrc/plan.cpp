@@ -11,42 +11,77 @@ struct RowTile {
   int32_t entry, row0, nrows, kv_hi;
 };
 
-// Splits each row tile's visible key range [0, kv_hi) into nearly equal chunks so that the items of
-// one kernel have similar cost and there are about `target` of them per KV head.
-void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk,
+// Splits each row tile's visible key range [0, kv_hi) into chunks so that the items of one kernel
+// have similar cost and there are about `target` of them per KV head.  All row tiles of an entry use
+// the same chunk boundaries (multiples of kv_tile): the workgroups that walk one chunk of one entry
+// read the same K/V tiles, so they are made neighbours in launch order (`group` = true) and, running
+// at the same time on the XCD of their KV head, fetch each tile from HBM once and from L2 after that.
+void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk, bool group,
                std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
   if (tiles.empty()) return;
   int64_t total = 0;
   for (const RowTile& t : tiles) total += t.kv_hi;
   int64_t chunk = std::max<int64_t>(min_chunk, (total + target - 1) / target);
   chunk = (chunk + kv_tile - 1) / kv_tile * kv_tile;
-  for (const RowTile& t : tiles) {
-    int32_t nsplit = (int32_t)((t.kv_hi + chunk - 1) / chunk);
+
+  struct Keyed {
+    DkItem it;
+    int64_t group_cost;
+    int32_t split;
+  };
+  std::vector<Keyed> keyed;
+  // tiles of one entry are consecutive in `tiles`
+  for (size_t b = 0; b < tiles.size();) {
+    size_t e = b;
+    int32_t hi_max = 0;
+    while (e < tiles.size() && tiles[e].entry == tiles[b].entry) hi_max = std::max(hi_max, tiles[e++].kv_hi);
+    int32_t nsplit = (int32_t)((hi_max + chunk - 1) / chunk);
     // avoid a last split that is only a sliver
-    if (nsplit > 1 && t.kv_hi - (int64_t)(nsplit - 1) * chunk < chunk / 4) --nsplit;
-    int64_t each = ((t.kv_hi + nsplit - 1) / nsplit + kv_tile - 1) / kv_tile * kv_tile;
-    nsplit = (int32_t)((t.kv_hi + each - 1) / each);
-    int32_t part0 = -1;
-    if (nsplit > 1) {
-      part0 = (int32_t)*part_rows;
-      *part_rows += (int64_t)nsplit * t.nrows;
-      merges->push_back({t.entry, t.row0, t.nrows, part0, nsplit, {0, 0, 0}});
+    if (nsplit > 1 && hi_max - (int64_t)(nsplit - 1) * chunk < chunk / 4) --nsplit;
+    const int64_t each = ((hi_max + nsplit - 1) / nsplit + kv_tile - 1) / kv_tile * kv_tile;
+    const size_t first = keyed.size();
+    for (size_t k = b; k < e; ++k) {
+      const RowTile& t = tiles[k];
+      int32_t ns = (int32_t)((t.kv_hi + each - 1) / each);
+      if (ns > 1 && t.kv_hi - (int64_t)(ns - 1) * each < each / 4) --ns;  // the previous chunk takes the sliver
+      int32_t part0 = -1;
+      if (ns > 1) {
+        part0 = (int32_t)*part_rows;
+        *part_rows += (int64_t)ns * t.nrows;
+        merges->push_back({t.entry, t.row0, t.nrows, part0, ns, {0, 0, 0}});
+      }
+      for (int32_t sp = 0; sp < ns; ++sp) {
+        DkItem it{};
+        it.entry = t.entry;
+        it.row0 = t.row0;
+        it.nrows = t.nrows;
+        it.kv_lo = (int32_t)(sp * each);
+        it.kv_hi = sp + 1 == ns ? t.kv_hi : (int32_t)((sp + 1) * each);
+        it.part_row0 = ns > 1 ? part0 + sp * t.nrows : -1;
+        keyed.push_back({it, 0, sp});
+      }
     }
-    for (int32_t s = 0; s < nsplit; ++s) {
-      DkItem it{};
-      it.entry = t.entry;
-      it.row0 = t.row0;
-      it.nrows = t.nrows;
-      it.kv_lo = (int32_t)(s * each);
-      it.kv_hi = (int32_t)std::min<int64_t>(t.kv_hi, (s + 1) * each);
-      it.part_row0 = nsplit > 1 ? part0 + s * t.nrows : -1;
-      items->push_back(it);
-    }
+    // cost of each (entry, chunk) group
+    std::vector<int64_t> cost(nsplit + 1, 0);
+    for (size_t k = first; k < keyed.size(); ++k)
+      cost[keyed[k].split] += (int64_t)(keyed[k].it.kv_hi - keyed[k].it.kv_lo) * keyed[k].it.nrows;
+    for (size_t k = first; k < keyed.size(); ++k) keyed[k].group_cost = cost[keyed[k].split];
+    b = e;
   }
   // longest first, so the tail of the launch is made of the cheapest items
-  std::stable_sort(items->begin(), items->end(), [](const DkItem& a, const DkItem& b) {
-    return (int64_t)(a.kv_hi - a.kv_lo) * a.nrows > (int64_t)(b.kv_hi - b.kv_lo) * b.nrows;
-  });
+  if (group) {
+    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
+      if (a.group_cost != b.group_cost) return a.group_cost > b.group_cost;
+      if (a.it.entry != b.it.entry) return a.it.entry < b.it.entry;
+      if (a.split != b.split) return a.split < b.split;
+      return a.it.row0 > b.it.row0;
+    });
+  } else {
+    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
+      return (int64_t)(a.it.kv_hi - a.it.kv_lo) * a.it.nrows > (int64_t)(b.it.kv_hi - b.it.kv_lo) * b.it.nrows;
+    });
+  }
+  for (const Keyed& k : keyed) items->push_back(k.it);
 }
 }  // namespace
 
@@ -90,9 +125,10 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
       }
     }
   }
-  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, &p->tile_items, &p->merges, &p->part_rows);
-  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, &p->stream_items, &p->merges,
+  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, &p->tile_items, &p->merges,
             &p->part_rows);
+  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, &p->stream_items,
+            &p->merges, &p->part_rows);
 
   size_t off = 0;
   p->off_entries = off;
