@@ -180,15 +180,32 @@ def make_workload(name):
     raise ValueError(name)
 
 
+def measured_traffic(name):
+    """HBM bytes per launch of the workload's dominant kernel as read by rocprofv3 counters (None if never profiled).
+
+    The counters cannot be read from inside this process; the readings of the profiled runs of this same command
+    are kept as text under profiles/ and quoted here."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == name:
+                return int(f[2]) + int(f[3])
+    except OSError:
+        pass
+    return None
+
+
 def roofline_for(name, flops, nbytes, kernel_ms):
     sec = kernel_ms * 1e-3
+    traffic = measured_traffic(name)
     if name in ("c5", "c2"):
         ach = nbytes / sec / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic}
     ach = flops / sec / 1e12
     return {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+            "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
 
 
 def cpu_baseline(sc, budget_s):
