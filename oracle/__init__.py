@@ -7,7 +7,9 @@ smoke check and the benchmark's CPU-baseline leg may use it.
 
 Parity status: every function here is pinned by the CPU test-suite (closed
 forms, brute force, a second independently written full recompute, a library
-attention routine, the paper's printed arithmetic).  The absolute output values
+attention routine, the paper's printed arithmetic; the verify step by a
+brute-force loop, hand cases and the equivalence with token-by-token
+decoding that the paper calls correctness-preserving).  The absolute output values
 of the five benchmark workloads are printed nowhere in the paper, so those are
 pinned only through these invariants.
 """
@@ -19,6 +21,7 @@ from .attention import (  # noqa: F401
     decode_one,
 )
 from .pool import OraclePool, OracleError  # noqa: F401
+from .verify import greedy_argmax, verify_accept, verify_batch, sequential_greedy  # noqa: F401
 from .costmodel import (  # noqa: F401
     prompt_lengths,
     turn_speedup,
