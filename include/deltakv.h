@@ -164,6 +164,33 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
                         int64_t workspace_bytes, void* stream);
 
 /*
+ * verify_greedy: the step after the Delta = k+1 verification pass of paper Alg. 2, on the device
+ * (Sec. 3.8: greedy sampling is an argmax over the vocabulary logits, batched over the k+1
+ * speculated positions, and the host never scans the logits).  Slot b's batch rows
+ * cu_delta[b] .. cu_delta[b+1]-1 hold the tokens [G_last, draft 0, ..., draft k-1]; logits row s is
+ * the model's output after batch position s.  For every row the kernel takes the argmax (ties: lowest
+ * token id; a NaN logit counts as +infinity), then accepts drafts front to back while
+ * argmax(row s) == draft s.  With `a` accepted drafts:
+ *   n_keep[b]     = 1 + a   -- how many of the slot's k+1 new cells stay (the n_accept of dk_kv_append,
+ *                              or len - (k+1) + n_keep as the new_len of dk_seq_trim)
+ *   next_token[b] = argmax(row a), the token to emit next
+ * Slots without rows get n_keep 0 and next_token -1.  Stateless: needs no pool.
+ *   cu_delta_dev  DEVICE int32 [n_seqs+1]  (a device copy of the batch's cu_delta)
+ *   logits        DEVICE [total_rows, row_stride] of dtype DK_F32 / DK_BF16, 16-byte aligned, row_stride
+ *                 (elements, >= vocab) a multiple of 16 bytes; DK_ERR_UNSUPPORTED otherwise
+ *   batch_tokens  DEVICE int32 [total_rows]
+ *   argmax_out    DEVICE int32 [total_rows] or NULL
+ *   n_keep_out, next_token_out  DEVICE int32 [n_seqs]
+ *   workspace     DEVICE, 256-byte aligned, >= dk_verify_workspace_bytes(total_rows, vocab, dtype)
+ * total_rows <= 65535, vocab < 2^31.  Asynchronous on `stream`; allocates nothing.
+ */
+int32_t dk_verify_workspace_bytes(int32_t total_rows, int64_t vocab, int32_t dtype, int64_t* bytes_out);
+int32_t dk_verify_greedy(int32_t n_seqs, int32_t total_rows, const int32_t* cu_delta_dev, const void* logits,
+                         int32_t dtype, int64_t vocab, int64_t row_stride, const int32_t* batch_tokens,
+                         int32_t* argmax_out, int32_t* n_keep_out, int32_t* next_token_out, void* workspace,
+                         int64_t workspace_bytes, void* stream);
+
+/*
  * Probes used by the tests to check bookkeeping bit for bit.
  * dk_seq_cells: physical cell index of each logical position (HOST int64 [cap]); writes
  *   min(len, cap) entries.  Aliased positions report the donor's cells.

@@ -57,6 +57,10 @@ SIGNATURES = {
     "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
     "dk_seq_gather": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_pool_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P]),
+    "dk_verify_workspace_bytes": (C.c_int32, [C.c_int32, C.c_int64, C.c_int32, _I64P]),
+    "dk_verify_greedy": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                     C.c_void_p]),
     "dk_set_attend_variant": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_set_attend_timing": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_attend_times": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, _I32P]),
@@ -199,6 +203,23 @@ def delta_attend(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=
     _check(lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new), float(scale),
                                  _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)),
            "delta_attend", pool)
+
+
+def verify_workspace_bytes(total_rows: int, vocab: int, dtype: int) -> int:
+    out = C.c_int64()
+    _check(lib().dk_verify_workspace_bytes(int(total_rows), int(vocab), int(dtype), C.byref(out)),
+           "verify_workspace_bytes")
+    return out.value
+
+
+def verify_greedy(n_seqs: int, total_rows: int, cu_delta_dev, logits, dtype: int, vocab: int, row_stride: int,
+                  batch_tokens, n_keep_out, next_token_out, workspace, argmax_out=None, stream=None) -> None:
+    """All tensors are device tensors; nothing is synchronised."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dk_verify_greedy(int(n_seqs), int(total_rows), _ptr(cu_delta_dev), _ptr(logits), int(dtype),
+                                  int(vocab), int(row_stride), _ptr(batch_tokens), _ptr(argmax_out),
+                                  _ptr(n_keep_out), _ptr(next_token_out), _ptr(workspace), ws_bytes,
+                                  _stream(stream)), "verify_greedy")
 
 
 def seq_gather(pool, slot: int, k_out, v_out, stream=None) -> None:

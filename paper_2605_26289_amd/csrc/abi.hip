@@ -347,6 +347,35 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   return DK_OK;
 }
 
+int32_t dk_verify_workspace_bytes(int32_t total_rows, int64_t vocab, int32_t dtype, int64_t* bytes_out) {
+  if (!bytes_out || total_rows < 0 || vocab <= 0 || vocab > INT32_MAX) return DK_ERR_INVALID;
+  if (dtype != DK_F32 && dtype != DK_BF16) return DK_ERR_UNSUPPORTED;
+  *bytes_out = dk::verify_workspace_bytes(total_rows, vocab, dtype);
+  return DK_OK;
+}
+
+int32_t dk_verify_greedy(int32_t n_seqs, int32_t total_rows, const int32_t* cu_delta_dev, const void* logits,
+                         int32_t dtype, int64_t vocab, int64_t row_stride, const int32_t* batch_tokens,
+                         int32_t* argmax_out, int32_t* n_keep_out, int32_t* next_token_out, void* workspace,
+                         int64_t workspace_bytes, void* stream) {
+  if (n_seqs < 0 || total_rows < 0 || vocab <= 0 || vocab > INT32_MAX || row_stride < vocab) return DK_ERR_INVALID;
+  if (dtype != DK_F32 && dtype != DK_BF16) return DK_ERR_UNSUPPORTED;
+  if (n_seqs == 0) return DK_OK;
+  if (total_rows > 65535) return DK_ERR_UNSUPPORTED;
+  if (!cu_delta_dev || !n_keep_out || !next_token_out) return DK_ERR_INVALID;
+  if (total_rows > 0 && (!logits || !batch_tokens)) return DK_ERR_INVALID;
+  const int64_t elem = dtype == DK_BF16 ? 2 : 4;
+  // rows are read with 16-byte loads
+  if (((uintptr_t)logits & 15) || (row_stride * elem) % 16) return DK_ERR_UNSUPPORTED;
+  if (!workspace || ((uintptr_t)workspace & 255) ||
+      workspace_bytes < dk::verify_workspace_bytes(total_rows, vocab, dtype))
+    return DK_ERR_WORKSPACE;
+  hipError_t e = dk::launch_verify_greedy(n_seqs, total_rows, cu_delta_dev, logits, dtype, vocab, row_stride,
+                                          batch_tokens, argmax_out, n_keep_out, next_token_out, workspace,
+                                          (hipStream_t)stream);
+  return e == hipSuccess ? DK_OK : DK_ERR_HIP;
+}
+
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant) {
   if (!pool || variant < 0 || variant > 1) return DK_ERR_INVALID;
   pool->variant = variant;

@@ -44,4 +44,11 @@ hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t 
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
 hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, hipStream_t stream);
 
+// Greedy verification (argmax per logits row, accepted-draft count and next token per slot).
+int64_t verify_workspace_bytes(int32_t total_rows, int64_t vocab, int32_t dtype);
+hipError_t launch_verify_greedy(int32_t n_seqs, int32_t total_rows, const int32_t* cu_delta_dev, const void* logits,
+                                int32_t dtype, int64_t vocab, int64_t row_stride, const int32_t* batch_tokens,
+                                int32_t* argmax_out, int32_t* n_keep_out, int32_t* next_token_out, void* workspace,
+                                hipStream_t stream);
+
 }  // namespace dk
