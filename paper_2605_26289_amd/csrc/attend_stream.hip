@@ -30,90 +30,118 @@ struct RowState {
   float l[MB];      // this lane's share of the weight sum (the other half-wave holds the rest)
 };
 
-// Q as B operand: lane (row l%32 of block mb, half l/32) holds Q[row][ks*16 + 8*(l/32) .. +7].
-template <int MB, int KB>
-__device__ __forceinline__ void compute_tile(const char* k_lds, const char* v_lds, const bf16x8 (&qf)[MB][8],
-                                             RowState<MB>& st, const int (&limit)[MB], float c, int lane, int cnt,
-                                             int pos, bool need_mask) {
-  f32x16 s[KB][MB];
+// All MFMA operand fragments of one 32-key tile, read out of its LDS stage in one go: once they are in
+// registers the stage can take the next HBM load while the tile is still being computed.
+struct TileFrags {
+  bf16x8 k[8];     // [depth step]
+  bf16x8 v[2][4];  // [key step][depth block]
+};
+__device__ __forceinline__ void read_frags(const char* k_lds, const char* v_lds, int lane, TileFrags& f) {
+  const uint32_t koff = k_lane_off(lane), voff = v_lane_off(lane);
 #pragma unroll
-  for (int kb = 0; kb < KB; ++kb)
+  for (int ks = 0; ks < 8; ++ks) f.k[ks] = read_k_frag(k_lds, koff, 0, ks);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][mb][r] = 0.f;
+    for (int db = 0; db < 4; ++db) f.v[j][db] = read_v_frag(v_lds, voff, j, db);
+}
 
+constexpr float STREAM_RESCALE_SLACK = 8.f;  // log2 units, as in the tile kernel
+
+__device__ __forceinline__ float stream_max3(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
+// One 32-key tile against MB*32 query rows, operands in registers: S^T, online softmax, O^T update.
+// Q as B operand: lane (row l%32 of block mb, half l/32) holds Q[row][ks*16 + 8*(l/32) .. +7].
+template <int MB>
+__device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&qf)[MB][8], RowState<MB>& st,
+                                             const int (&limit)[MB], float c, int lane, int cnt, int pos,
+                                             bool need_mask) {
+  f32x16 s[MB];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    bf16x8 a[KB];
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) a[kb] = read_k_frag(k_lds, k_lane_off(lane), kb, ks);
+    for (int r = 0; r < 16; ++r) s[mb][r] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+  for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-        s[kb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kb], qf[mb][ks], s[kb][mb], 0, 0, 0);
-  }
+    for (int mb = 0; mb < MB; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.k[ks], qf[mb][ks], s[mb], 0, 0, 0);
 
   const int h = lane >> 5;
   if (need_mask) {
-    // accumulator r of key block kb is key kb*32 + 8*(r/4) + 4h + r%4 of the tile
+    // accumulator r is key 8*(r/4) + 4h + r%4 of the tile
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const int lim = min(cnt - 1, limit[mb] - pos);
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key > lim) s[kb][mb][r] = -INFINITY;
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int key = 8 * (r >> 2) + 4 * h + (r & 3);
+        if (key > lim) s[mb][r] = -INFINITY;
+      }
     }
   }
 
-  bf16x8 pf[MB][2 * KB];
+  // row maxima; the reference maximum of a row is only raised (and O, l rescaled) when the tile outgrows
+  // it by more than the slack, so after the first tiles the 128 multiplies on O are rare
+  float mx[MB];
+  bool grow = false;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    float mx = -INFINITY;
+    float v = stream_max3(s[mb][0], s[mb][1], s[mb][2]);
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+    for (int r = 3; r < 15; r += 2) v = stream_max3(v, s[mb][r], s[mb][r + 1]);
+    v = fmaxf(v, s[mb][15]);
+    v = fmaxf(v, __shfl_xor(v, 32));
+    mx[mb] = v * c;
+    grow |= mx[mb] > st.m[mb] + STREAM_RESCALE_SLACK;
+  }
+  if (__builtin_amdgcn_ballot_w64(grow) != 0) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][mb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mn = fmaxf(st.m[mb], mx * c);
-    const float ms = (mn == -INFINITY) ? 0.f : mn;  // every key so far masked: keep the arithmetic finite
-    const float alpha = __builtin_amdgcn_exp2f(st.m[mb] - ms);
-    float rs = 0.f;
+    for (int mb = 0; mb < MB; ++mb) {
+      const float mn = fmaxf(st.m[mb], mx[mb]);
+      const float mz = (mn == -INFINITY) ? 0.f : mn;  // every key so far masked: keep the arithmetic finite
+      const float alpha = __builtin_amdgcn_exp2f(st.m[mb] - mz);
+      st.m[mb] = mn;
+      st.l[mb] *= alpha;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][mb][r], c, -ms));
-        rs += p;
-        s[kb][mb][r] = p;
+        for (int r = 0; r < 16; ++r) st.o[db][mb][r] *= alpha;
+    }
+  }
+
+  bf16x8 pf[MB][2];
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  bf16x2 ones;
+  ones[0] = (__bf16)1.0f;
+  ones[1] = (__bf16)1.0f;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const float ms = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        bf16x2 pw;
+        pw[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w], c, -ms));
+        pw[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w + 1], c, -ms));
+        // the weight sum takes the rounded weights, the ones the PV product uses
+        st.l[mb] = __builtin_amdgcn_fdot2_f32_bf16(pw, ones, st.l[mb], false);
+        pf[mb][j][2 * w] = pw[0];
+        pf[mb][j][2 * w + 1] = pw[1];
       }
-    st.l[mb] = st.l[mb] * alpha + rs;
-    st.m[mb] = mn;
+  }
+
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) st.o[db][mb][r] *= alpha;
-#pragma unroll
-    for (int j = 0; j < 2 * KB; ++j)
-#pragma unroll
-      for (int t = 0; t < 8; ++t) pf[mb][j][t] = (__bf16)s[j >> 1][mb][8 * (j & 1) + t];
-  }
-
-#pragma unroll
-  for (int j = 0; j < 2 * KB; ++j) {
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      const bf16x8 vf = read_v_frag(v_lds, v_lane_off(lane), j, db);
-#pragma unroll
       for (int mb = 0; mb < MB; ++mb)
-        st.o[db][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb][j], st.o[db][mb], 0, 0, 0);
-    }
-  }
+        st.o[db][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.v[j][db], pf[mb][j], st.o[db][mb], 0, 0, 0);
 }
 
 // Accumulator r of depth block db is depth db*32 + 8*(r/4) + 4h + r%4: four consecutive depths per r/4.
@@ -161,9 +189,12 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c) {
   const int hi = min(it.kv_hi, lo + per);
   char* my = smem + wave * STREAM_WAVE_BYTES;
 
+  // Two private stages per wavefront.  A tile's fragments are read into registers as soon as it has
+  // landed and its stage is handed to the load of the tile after next at once, so two tiles (32 KiB per
+  // wavefront) are in flight while one is being computed -- with only the other stage loading, HBM
+  // latency would not be covered.
   KvCursor cur{c.segs, e.seg_begin, e.seg_end, lo, hi};
-  KvTile tc, tn;
-  bool have = cur.next(c, g, STREAM_KT, tc);
+  KvTile t0, t1, t2;  // being computed, next, the one after
   auto issue = [&](const KvTile& t, int stage) {
     char* kl = my + stage * STREAM_STAGE_BYTES;
     char* vl = kl + STREAM_KT * ROW_BYTES;
@@ -172,21 +203,28 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c) {
 #pragma unroll
     for (int b = 0; b < 8; ++b) load_rows4<true>(t.v, t.stride, t.cnt, vl, b, lane);
   };
-  if (have) issue(tc, 0);
+  bool have0 = cur.next(c, g, STREAM_KT, t0);
+  bool have1 = have0 && cur.next(c, g, STREAM_KT, t1);
+  if (have0) issue(t0, 0);
+  if (have1) issue(t1, 1);
   int stage = 0;
-  while (have) {
-    const bool have_next = cur.next(c, g, STREAM_KT, tn);
-    if (have_next) {
-      issue(tn, stage ^ 1);
-      wait_vmcnt<16>();
-    } else {
-      wait_vmcnt<0>();
-    }
+  TileFrags fr;
+  while (have0) {
+    if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
     const char* kl = my + stage * STREAM_STAGE_BYTES;
-    const bool need_mask = tc.cnt < STREAM_KT || tc.pos + STREAM_KT - 1 > min_limit;
-    compute_tile<MB, 1>(kl, kl + STREAM_KT * ROW_BYTES, qf, st, limit, c.c, lane, tc.cnt, tc.pos, need_mask);
-    tc = tn;
-    have = have_next;
+    read_frags(kl, kl + STREAM_KT * ROW_BYTES, lane, fr);
+    const bool have2 = have1 && cur.next(c, g, STREAM_KT, t2);
+    if (have2) {
+      // the stage may only be overwritten once every fragment read has returned
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      issue(t2, stage);
+    }
+    const bool need_mask = t0.cnt < STREAM_KT || t0.pos + STREAM_KT - 1 > min_limit;
+    compute_tile<MB>(fr, qf, st, limit, c.c, lane, t0.cnt, t0.pos, need_mask);
+    t0 = t1;
+    t1 = t2;
+    have0 = have1;
+    have1 = have2;
     stage ^= 1;
   }
 
