@@ -88,19 +88,6 @@ __device__ __forceinline__ float max_halves(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
 }
-// Two probabilities -> one register of bf16 (RNE); their sum, as rounded, goes into the weight sum so
-// that numerator and denominator of the softmax see the same weights.
-__device__ __forceinline__ uint32_t pack_add(float p0, float p1, float& l) {
-  bf16x2 w;
-  w[0] = (__bf16)p0;
-  w[1] = (__bf16)p1;
-  bf16x2 ones;
-  ones[0] = (__bf16)1.0f;
-  ones[1] = (__bf16)1.0f;
-  l = __builtin_amdgcn_fdot2_f32_bf16(w, ones, l, false);
-  return __builtin_bit_cast(uint32_t, w);
-}
-
 // The reference maximum of a row only moves when its maximum grew by more than this (log2 units):
 // after the first tiles the rescale of O is rare, and the weights stay below 2^8.
 constexpr float RESCALE_SLACK = 8.f;
@@ -210,11 +197,10 @@ __device__ __forceinline__ void lane_offsets(uint32_t (&vo)[4], int wave, int la
 // ---- pipelined step ----------------------------------------------------------------------------------
 //   MFMA  0..31  S^T(next): depth step i/4, key block (i/2)%2, row block i%2
 //   MFMA 32..63  PV(prev):  key step j = (i-32)/8, depth block ((i-32)/2)%4, row block i%2
-// VALU work of the current tile goes in pairs of elements (one bf16 register of P): pair q is
-// exponentiated during slots 2q and 2q+1 and packed in slot 2q+2, after that slot's first multiply-add
-// (so that the pack never directly follows the v_exp_f32 whose result it reads).
-// LDS reads: K fragments one depth step ahead; V fragments two (j, db) pairs at a time, four slots
-// ahead of their first use.  Each group is awaited once, at its first use.
+// VALU work of the current tile: slot i exponentiates element i and scales element i+1; every second
+// slot packs the pair finished one slot earlier; the row sum takes each weight one slot after its exp2.
+// LDS reads: K fragments two depth steps (eight slots) ahead; V fragments two (j, db) pairs at a time,
+// eight slots ahead of their first use.  Each group is awaited once, at its first use.
 struct FastStep {
   const char* k_lds;  // K tile t+1
   const char* v_lds;  // V tile t-1
@@ -229,31 +215,49 @@ struct FastStep {
   float c;
   uint32_t koff, voff;
   float mxn[MB];
-  float xe;         // scaled score waiting for its exp2
+  float xe[2];      // scaled scores waiting for their exp2
   float pe[2][2];   // [pair parity][element]
-  bf16x8 kf[2][2];  // [depth-step parity][key block]
-  bf16x8 vf[4];     // ring over the (j, db) pairs
+  bf16x8 kf[3][2];  // [depth step % 3][key block]
+  bf16x8 vf[6];     // ring over the (j, db) pairs
 
-  template <int Q, int HALF>
+  // Softmax element E (0..63) of the current tile, in the order PV will consume them: pair E/2 is one
+  // bf16 register of P.  The four instructions of an element's chain (multiply-add, exp2, pack, row sum)
+  // run in different slots, each at least one slot after the one that feeds it, so none of them waits
+  // on its predecessor's result.
+  template <int E>
   __device__ __forceinline__ void scale() {
+    constexpr int Q = E >> 1, HALF = E & 1;
     constexpr int grp = Q >> 2, w = Q & 3;
     constexpr int mb = grp & 1, j = grp >> 1;
     constexpr int kb = j >> 1, r = 8 * (j & 1) + 2 * w + HALF;
-    xe = __builtin_fmaf(sc[kb][mb][r], c, -ms[mb]);
+    xe[E & 1] = __builtin_fmaf(sc[kb][mb][r], c, -ms[mb]);
+    pin(xe[E & 1]);
   }
-  template <int Q, int HALF>
+  template <int E>
   __device__ __forceinline__ void expo() {
-    float p = __builtin_amdgcn_exp2f(xe);
+    constexpr int mb = (E >> 3) & 1;
+    float p = __builtin_amdgcn_exp2f(xe[E & 1]);
     pin(p);
-    pe[Q & 1][HALF] = p;
+    pe[(E >> 1) & 1][E & 1] = p;
+  }
+  // Row sums are plain fp32 adds of the unrounded weights, one slot after the exp2.  (Summing the rounded
+  // pair with a v_dot2 would be half the instructions, but the dot instructions run on the matrix pipe:
+  // measured, each one stalls until the MFMA in flight has drained.)
+  template <int E>
+  __device__ __forceinline__ void rowsum() {
+    constexpr int mb = (E >> 3) & 1;
+    st.l[mb] += pe[(E >> 1) & 1][E & 1];
+    pin(st.l[mb]);
   }
   template <int Q>
   __device__ __forceinline__ void pack() {
     constexpr int grp = Q >> 2, w = Q & 3;
     constexpr int mb = grp & 1, j = grp >> 1;
-    uint32_t word = pack_add(pe[Q & 1][0], pe[Q & 1][1], st.l[mb]);
+    bf16x2 pw;
+    pw[0] = (__bf16)pe[Q & 1][0];
+    pw[1] = (__bf16)pe[Q & 1][1];
+    const uint32_t word = __builtin_bit_cast(uint32_t, pw);
     pin(word);
-    pin(st.l[mb]);
     pc[mb][j][w] = word;
   }
   // row maxima of the next tile: op Z of 32 chained max3 (Z % 2 = row block), then the half-wave exchange
@@ -276,7 +280,7 @@ struct FastStep {
   }
   template <int PAIR>
   __device__ __forceinline__ void read_v_pair() {
-    vf[PAIR & 3] = read_v_frag(v_lds, voff, PAIR >> 2, PAIR & 3);
+    vf[PAIR % 6] = read_v_frag(v_lds, voff, PAIR >> 2, PAIR & 3);
   }
 
   template <int I>
@@ -284,41 +288,40 @@ struct FastStep {
     if constexpr (I < 32) {
       constexpr int ks = I >> 2, kb = (I >> 1) & 1, mb = I & 1;
       if constexpr ((I & 3) == 0) {
-        if constexpr (ks + 1 < 8) {
-          kf[(ks + 1) & 1][0] = read_k_frag(k_lds, koff, 0, ks + 1);
-          kf[(ks + 1) & 1][1] = read_k_frag(k_lds, koff, 1, ks + 1);
+        if constexpr (ks + 2 < 8) {
+          kf[(ks + 2) % 3][0] = read_k_frag(k_lds, koff, 0, ks + 2);
+          kf[(ks + 2) % 3][1] = read_k_frag(k_lds, koff, 1, ks + 2);
         }
         // one wait for both key blocks of this depth step
-        asm volatile("" : : "a"(kf[ks & 1][0]), "a"(kf[ks & 1][1]));
+        asm volatile("" : : "a"(kf[ks % 3][0]), "a"(kf[ks % 3][1]));
       }
       if constexpr (ks == 0) mfma_s_first(sn[kb][mb], kf[0][kb], qf[mb][0]);
-      else mfma_s(sn[kb][mb], kf[ks & 1][kb], qf[mb][ks]);
-      if constexpr (I == 28) {
+      else mfma_s(sn[kb][mb], kf[ks % 3][kb], qf[mb][ks]);
+      if constexpr (I == 24) {
         read_v_pair<0>();
         read_v_pair<1>();
+      }
+      if constexpr (I == 28) {
+        read_v_pair<2>();
+        read_v_pair<3>();
       }
     } else {
       constexpr int pair = (I - 32) >> 1, mb = I & 1;  // pair = j * 4 + db
       constexpr int j = pair >> 2, db = pair & 3;
       if constexpr (((I - 32) & 3) == 0) {
-        if constexpr (pair + 2 < 16) {
-          read_v_pair<pair + 2>();
-          read_v_pair<pair + 3>();
+        if constexpr (pair + 4 < 16) {
+          read_v_pair<pair + 4>();
+          read_v_pair<pair + 5>();
         }
-        asm volatile("" : : "a"(vf[pair & 3]), "a"(vf[(pair + 1) & 3]));
+        asm volatile("" : : "a"(vf[pair % 6]), "a"(vf[(pair + 1) % 6]));
       }
-      mfma_o(st.o[db][mb], vf[pair & 3], pp[mb][j]);
+      mfma_o(st.o[db][mb], vf[pair % 6], pp[mb][j]);
     }
     // softmax of the current tile
-    constexpr int q = I >> 1;
-    if constexpr ((I & 1) == 0) {
-      scale<q, 0>();
-      expo<q, 0>();
-      if constexpr (q > 0) pack<q - 1>();
-    } else {
-      scale<q, 1>();
-      expo<q, 1>();
-    }
+    expo<I>();
+    if constexpr (I + 1 < 64) scale<I + 1>();
+    if constexpr (I >= 1) rowsum<I - 1>();
+    if constexpr ((I & 1) == 0 && I >= 2) pack<I / 2 - 1>();
     // HBM -> LDS loads of later tiles
     if constexpr ((I & 1) == 1 && I < 16) issue_one<(I - 1) / 2>(ld);
     // row maxima of the next tile
@@ -329,6 +332,10 @@ struct FastStep {
   template <int... Is>
   __device__ __forceinline__ void run(std::integer_sequence<int, Is...>) {
     (slot<Is>(), ...);
+  }
+  template <int BASE, int... Is>
+  __device__ __forceinline__ void run_from(std::integer_sequence<int, Is...>) {
+    (slot<BASE + Is>(), ...);
   }
 };
 
@@ -532,12 +539,24 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
       }
       pending = true;
     }
+    DK_PROF_T(t2);
     {
       FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, ms, c.c, koff, voff};
       f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
       f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
+      f.kf[1][0] = read_k_frag(k_lds, koff, 0, 1);
+      f.kf[1][1] = read_k_frag(k_lds, koff, 1, 1);
       __builtin_amdgcn_sched_barrier(0);
+      f.scale<0>();
+#ifdef DK_PROF
+      f.run(std::make_integer_sequence<int, 32>{});
+      DK_PROF_T(tm);
+      DK_PROF_ADD(1, tm - t2);
+      f.run_from<32>(std::make_integer_sequence<int, 32>{});
+#else
       f.run(std::make_integer_sequence<int, 64>{});
+#endif
+      f.rowsum<63>();
       f.pack<31>();
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) mx[mb] = f.mxn[mb];
@@ -574,6 +593,7 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
 #ifdef DK_PROF
   if (lane == 0) {
     atomicAdd(&g_prof[0], (unsigned long long)(__builtin_readcyclecounter() - pstart));
+    atomicAdd(&g_prof[2], (unsigned long long)pacc[1]);
     atomicAdd(&g_prof[3], (unsigned long long)pacc[2]);
     atomicAdd(&g_prof[4], (unsigned long long)pacc[3]);
     atomicAdd(&g_prof[6], (unsigned long long)(wall_clock64() - wstart));
