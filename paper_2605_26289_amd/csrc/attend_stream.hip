@@ -114,25 +114,21 @@ __device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&
   }
 
   bf16x8 pf[MB][2];
-  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-  bf16x2 ones;
-  ones[0] = (__bf16)1.0f;
-  ones[1] = (__bf16)1.0f;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     const float ms = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
+    float rs[2] = {0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        bf16x2 pw;
-        pw[0] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w], c, -ms));
-        pw[1] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w + 1], c, -ms));
-        // the weight sum takes the rounded weights, the ones the PV product uses
-        st.l[mb] = __builtin_amdgcn_fdot2_f32_bf16(pw, ones, st.l[mb], false);
-        pf[mb][j][2 * w] = pw[0];
-        pf[mb][j][2 * w + 1] = pw[1];
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w], c, -ms));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][8 * j + 2 * w + 1], c, -ms));
+        rs[(j * 4 + w) & 1] += p0 + p1;  // (no v_dot2 here: the dot instructions queue behind the MFMAs)
+        pf[mb][j][2 * w] = (__bf16)p0;
+        pf[mb][j][2 * w + 1] = (__bf16)p1;
       }
+    st.l[mb] += rs[0] + rs[1];
   }
 
 #pragma unroll
