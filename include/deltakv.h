@@ -191,6 +191,75 @@ int32_t dk_verify_greedy(int32_t n_seqs, int32_t total_rows, const int32_t* cu_d
                          int64_t workspace_bytes, void* stream);
 
 /*
+ * Radix prefix cache and the per-turn procedure of paper Alg. 1 (Sec. 3.3), HOST only.  The trie is keyed
+ * by token ids; a node owns a token segment and names a donor sequence (a slot of the pool's session
+ * region that aliases the saver's cells) holding the whole path down to it.
+ *   dk_radix_create   cell_budget: most cells the trie may hold (sum of its nodes' segment lengths, the
+ *                     "cell budget" of Sec. 3.2); keep_last: tokens that always go through the model even
+ *                     when the whole prompt is cached (1: the turn needs logits for its last position).
+ *                     Destroy the trie before its pool; destroying it releases the donor slots.
+ *   dk_radix_begin_turn  Alg. 1 lines 1-5: (m, donor) = longest cached prefix of tokens[0..n_tokens), capped at
+ *                     n_tokens - keep_last; if m > 0, SeqAlias(donor, slot, 0, m) -- so `slot` must be acquired
+ *                     and empty (errors of dk_seq_alias are passed on).  *n_past_out = m, the cells skipped this
+ *                     turn.  The caller then runs only tokens[m..] through dk_kv_append / dk_delta_attend.
+ *   dk_radix_save     Alg. 1 last line, once len(slot) >= n_tokens: walk the branch to its tip (splitting a node
+ *                     if the prompt diverges inside its segment) and append ONE node holding only the cells the
+ *                     trie does not have yet.  If that would exceed the budget, or no session slot is free, the
+ *                     leaf with the oldest touch is shed (never a node on this save's own path) until it fits;
+ *                     *saved_out (nullable) = 1 if the prompt is now cached to its end, 0 if room could not be
+ *                     made (not an error: the turn is unaffected).
+ *   dk_radix_stats    nodes, cells held, donor slots held, leaves shed so far (each pointer nullable).
+ *   dk_radix_evicted_path  token path (root to leaf end) of the index-th shed leaf, oldest first: *len_out =
+ *                     its length, at most cap tokens copied; DK_ERR_INVALID if there is no such leaf.
+ * Calls on one trie are serialised by a mutex of its own.
+ */
+typedef struct dk_radix dk_radix;
+int32_t dk_radix_create(dk_pool* pool, int64_t cell_budget, int32_t keep_last, dk_radix** radix_out);
+int32_t dk_radix_destroy(dk_radix* radix);
+int32_t dk_radix_begin_turn(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens,
+                            int64_t* n_past_out);
+int32_t dk_radix_save(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens, int32_t* saved_out);
+int32_t dk_radix_stats(dk_radix* radix, int64_t* nodes_out, int64_t* cells_out, int64_t* donors_out,
+                       int64_t* evictions_out);
+int32_t dk_radix_evicted_path(dk_radix* radix, int64_t index, int32_t* tokens_out, int64_t cap, int64_t* len_out);
+
+/*
+ * Prompt-lookup drafting, HOST only (paper Sec. 3.6, Alg. 2 line 1: LookupNgram(R, G_tail, l, N)).
+ * dk_pld_lookup: `recent` is the slot's recent token buffer (prompt followed by its own output).  Finds the
+ *   largest n in [min_match, max_match] such that the buffer's last n tokens also occur ending before its last
+ *   token (the most recent such occurrence among equals) and copies the tokens that followed it, at most
+ *   max_draft, to draft_out (HOST int32 [max_draft]).  *n_draft_out = k (0: no confident match),
+ *   *match_len_out (nullable) = n.
+ * dk_pld_gate: acceptance gating.  *ema_inout <- (1 - beta) ema + beta accepted / proposed (unchanged when
+ *   proposed == 0); *next_len_out = max_len if the average is >= threshold, else floor_len.
+ */
+int32_t dk_pld_lookup(const int32_t* recent, int64_t n_recent, int32_t min_match, int32_t max_match,
+                      int32_t max_draft, int32_t* draft_out, int32_t* n_draft_out, int32_t* match_len_out);
+int32_t dk_pld_gate(float* ema_inout, int32_t proposed, int32_t accepted, float beta, float threshold,
+                    int32_t floor_len, int32_t max_len, int32_t* next_len_out);
+
+/*
+ * Scheduler helpers, HOST only (paper Sec. 3.2).
+ * dk_prefill_chunk: workload-adaptive chunked prefill, chunk = clamp(n_batch / n_prefilling, 128, 4096); the
+ *   ceiling narrows to 1024 when a latency-sensitive request is co-resident under contention
+ *   (latency_sensitive != 0 and n_prefilling > 1).
+ * dk_fnv1a32: 32-bit FNV-1a of a byte string (the hash of Sec. 3.2's prefix grouping and of Eq. 7).
+ * dk_prefill_groups: prefix-aware grouped prefill.  Slot i has prompt tokens[i][0..n_tokens[i]) of which
+ *   n_past[i] are already cached through radix prefix prefix_id[i] (any id that is equal for equal cached
+ *   prefixes, e.g. the donor slot).  Slots with the same prefix_id and n_past whose next `window` tokens are
+ *   identical (found by FNV-1a of those tokens' bytes, confirmed by comparison) form a group: the first of
+ *   them in batch order is the leader (leader_out[i] = its index, i itself for leaders and ungrouped slots)
+ *   and shared_out[i] = length of the prefix follower i has in common with its leader (>= n_past[i] + window;
+ *   n_past[i] for leaders): after the leader has prefilled that far the follower takes it over with
+ *   dk_seq_alias(leader_slot, slot_i, 0, shared_out[i]) instead of a forward pass.  The paper's window is K = 8.
+ */
+int32_t dk_prefill_chunk(int64_t n_batch, int32_t n_prefilling, int32_t latency_sensitive, int64_t* chunk_out);
+int32_t dk_fnv1a32(const void* bytes, int64_t n_bytes, uint32_t* hash_out);
+int32_t dk_prefill_groups(int32_t n_slots, const int32_t* const* tokens, const int64_t* n_tokens,
+                          const int64_t* n_past, const int32_t* prefix_id, int32_t window, int32_t* leader_out,
+                          int64_t* shared_out);
+
+/*
  * Probes used by the tests to check bookkeeping bit for bit.
  * dk_seq_cells: physical cell index of each logical position (HOST int64 [cap]); writes
  *   min(len, cap) entries.  Aliased positions report the donor's cells.

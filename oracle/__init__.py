@@ -24,6 +24,7 @@ from .pool import OraclePool, OracleError  # noqa: F401
 from .verify import greedy_argmax, verify_accept, verify_batch, sequential_greedy  # noqa: F401
 from .pld import lookup_ngram, gate as pld_gate  # noqa: F401
 from .radix import OracleRadix  # noqa: F401
+from .sched import prefill_chunk, fnv1a32, prefill_groups  # noqa: F401
 from .costmodel import (  # noqa: F401
     prompt_lengths,
     turn_speedup,

@@ -61,6 +61,18 @@ SIGNATURES = {
     "dk_verify_greedy": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                      C.c_void_p]),
+    "dk_radix_create": (C.c_int32, [C.c_void_p, C.c_int64, C.c_int32, C.POINTER(C.c_void_p)]),
+    "dk_radix_destroy": (C.c_int32, [C.c_void_p]),
+    "dk_radix_begin_turn": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, C.c_int64, _I64P]),
+    "dk_radix_save": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, C.c_int64, _I32P]),
+    "dk_radix_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P, _I64P, _I64P]),
+    "dk_radix_evicted_path": (C.c_int32, [C.c_void_p, C.c_int64, _I32P, C.c_int64, _I64P]),
+    "dk_pld_lookup": (C.c_int32, [_I32P, C.c_int64, C.c_int32, C.c_int32, C.c_int32, _I32P, _I32P, _I32P]),
+    "dk_pld_gate": (C.c_int32, [C.POINTER(C.c_float), C.c_int32, C.c_int32, C.c_float, C.c_float, C.c_int32,
+                                C.c_int32, _I32P]),
+    "dk_prefill_chunk": (C.c_int32, [C.c_int64, C.c_int32, C.c_int32, _I64P]),
+    "dk_fnv1a32": (C.c_int32, [C.c_void_p, C.c_int64, C.POINTER(C.c_uint32)]),
+    "dk_prefill_groups": (C.c_int32, [C.c_int32, C.POINTER(_I32P), _I64P, _I64P, _I32P, C.c_int32, _I32P, _I64P]),
     "dk_set_attend_variant": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_set_attend_timing": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_attend_times": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, _I32P]),
@@ -220,6 +232,94 @@ def verify_greedy(n_seqs: int, total_rows: int, cu_delta_dev, logits, dtype: int
                                   int(vocab), int(row_stride), _ptr(batch_tokens), _ptr(argmax_out),
                                   _ptr(n_keep_out), _ptr(next_token_out), _ptr(workspace), ws_bytes,
                                   _stream(stream)), "verify_greedy")
+
+
+# -- host-only: radix prefix cache, prompt lookup, scheduler helpers ---------------------------------------
+def radix_create(pool, cell_budget: int, keep_last: int = 1) -> C.c_void_p:
+    out = C.c_void_p()
+    _check(lib().dk_radix_create(pool, int(cell_budget), int(keep_last), C.byref(out)), "radix_create")
+    return out
+
+
+def radix_destroy(radix) -> None:
+    _check(lib().dk_radix_destroy(radix), "radix_destroy")
+
+
+def radix_begin_turn(radix, slot: int, tokens) -> int:
+    t_arr, t_p = _i32(tokens)
+    out = C.c_int64()
+    _check(lib().dk_radix_begin_turn(radix, slot, t_p, len(t_arr), C.byref(out)), "radix_begin_turn")
+    return out.value
+
+
+def radix_save(radix, slot: int, tokens) -> bool:
+    t_arr, t_p = _i32(tokens)
+    out = C.c_int32()
+    _check(lib().dk_radix_save(radix, slot, t_p, len(t_arr), C.byref(out)), "radix_save")
+    return bool(out.value)
+
+
+def radix_stats(radix):
+    """(nodes, cells held, donor slots held, leaves shed so far)"""
+    v = [C.c_int64() for _ in range(4)]
+    _check(lib().dk_radix_stats(radix, *[C.byref(x) for x in v]), "radix_stats")
+    return tuple(x.value for x in v)
+
+
+def radix_evicted_path(radix, index: int):
+    n = C.c_int64()
+    _check(lib().dk_radix_evicted_path(radix, index, None, 0, C.byref(n)), "radix_evicted_path")
+    out = np.zeros(max(n.value, 1), dtype=np.int32)
+    _check(lib().dk_radix_evicted_path(radix, index, out.ctypes.data_as(_I32P), n.value, C.byref(n)),
+           "radix_evicted_path")
+    return out[: n.value].tolist()
+
+
+def pld_lookup(recent, min_match: int, max_match: int, max_draft: int):
+    """(draft tokens, matched n-gram length)"""
+    r_arr, r_p = _i32(recent)
+    draft = np.zeros(max(max_draft, 1), dtype=np.int32)
+    k, n = C.c_int32(), C.c_int32()
+    _check(lib().dk_pld_lookup(r_p, len(r_arr), min_match, max_match, max_draft, draft.ctypes.data_as(_I32P),
+                               C.byref(k), C.byref(n)), "pld_lookup")
+    return draft[: k.value].tolist(), n.value
+
+
+def pld_gate(ema: float, proposed: int, accepted: int, beta: float, threshold: float, floor_len: int, max_len: int):
+    """(new average, proposal length for the next step)"""
+    e, nxt = C.c_float(ema), C.c_int32()
+    _check(lib().dk_pld_gate(C.byref(e), proposed, accepted, beta, threshold, floor_len, max_len, C.byref(nxt)),
+           "pld_gate")
+    return e.value, nxt.value
+
+
+def prefill_chunk(n_batch: int, n_prefilling: int, latency_sensitive: bool = False) -> int:
+    out = C.c_int64()
+    _check(lib().dk_prefill_chunk(n_batch, n_prefilling, int(latency_sensitive), C.byref(out)), "prefill_chunk")
+    return out.value
+
+
+def fnv1a32(data: bytes) -> int:
+    out = C.c_uint32()
+    buf = C.create_string_buffer(data, len(data))
+    _check(lib().dk_fnv1a32(buf, len(data), C.byref(out)), "fnv1a32")
+    return out.value
+
+
+def prefill_groups(prompts, n_past, prefix_id, window: int = 8):
+    """(leader index per slot, tokens shared with the leader per slot)"""
+    n = len(prompts)
+    arrs = [np.ascontiguousarray(p, dtype=np.int32) for p in prompts]
+    ptrs = (_I32P * max(n, 1))(*[a.ctypes.data_as(_I32P) for a in arrs])
+    lens = np.asarray([len(a) for a in arrs], dtype=np.int64)
+    past = np.ascontiguousarray(n_past, dtype=np.int64)
+    pid = np.ascontiguousarray(prefix_id, dtype=np.int32)
+    leader = np.zeros(max(n, 1), dtype=np.int32)
+    shared = np.zeros(max(n, 1), dtype=np.int64)
+    _check(lib().dk_prefill_groups(n, ptrs, lens.ctypes.data_as(_I64P), past.ctypes.data_as(_I64P),
+                                   pid.ctypes.data_as(_I32P), window, leader.ctypes.data_as(_I32P),
+                                   shared.ctypes.data_as(_I64P)), "prefill_groups")
+    return leader[:n].tolist(), shared[:n].tolist()
 
 
 def seq_gather(pool, slot: int, k_out, v_out, stream=None) -> None:

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdeltakv.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["pool.cpp", "plan.cpp", "abi.hip", "kernels_basic.hip", "attend_stream.hip", "attend_tile.hip", "verify.hip"]
+SOURCES = ["pool.cpp", "plan.cpp", "radix.cpp", "pld.cpp", "sched.cpp", "abi.hip", "kernels_basic.hip", "attend_stream.hip", "attend_tile.hip", "verify.hip"]
 
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -13,6 +13,7 @@
 #include "kernels.hpp"
 #include "plan.hpp"
 #include "pool.hpp"
+#include "radix.hpp"
 
 namespace {
 
@@ -346,6 +347,54 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
     e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
+  return DK_OK;
+}
+
+}  // extern "C"
+
+struct dk_radix {
+  dk_pool* pool;
+  dk::Radix trie;
+  std::mutex mu;
+  dk_radix(dk_pool* p, int64_t budget, int32_t keep_last) : pool(p), trie(&p->meta, budget, keep_last) {}
+};
+
+extern "C" {
+
+int32_t dk_radix_create(dk_pool* pool, int64_t cell_budget, int32_t keep_last, dk_radix** radix_out) {
+  if (!pool || !radix_out || cell_budget <= 0 || keep_last < 0) return DK_ERR_INVALID;
+  *radix_out = new (std::nothrow) dk_radix(pool, cell_budget, keep_last);
+  return *radix_out ? DK_OK : DK_ERR_INVALID;
+}
+int32_t dk_radix_destroy(dk_radix* radix) {
+  if (!radix) return DK_ERR_INVALID;
+  delete radix;
+  return DK_OK;
+}
+int32_t dk_radix_begin_turn(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens,
+                            int64_t* n_past_out) {
+  if (!radix) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(radix->mu);
+  return radix->trie.begin_turn(slot, tokens, n_tokens, n_past_out);
+}
+int32_t dk_radix_save(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens, int32_t* saved_out) {
+  if (!radix) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(radix->mu);
+  return radix->trie.save(slot, tokens, n_tokens, saved_out);
+}
+int32_t dk_radix_stats(dk_radix* radix, int64_t* nodes_out, int64_t* cells_out, int64_t* donors_out,
+                       int64_t* evictions_out) {
+  if (!radix) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(radix->mu);
+  radix->trie.stats(nodes_out, cells_out, donors_out, evictions_out);
+  return DK_OK;
+}
+int32_t dk_radix_evicted_path(dk_radix* radix, int64_t index, int32_t* tokens_out, int64_t cap, int64_t* len_out) {
+  if (!radix || !len_out || cap < 0 || (cap > 0 && !tokens_out)) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> lk(radix->mu);
+  const int64_t n = radix->trie.evicted_path(index, tokens_out, cap);
+  if (n < 0) return DK_ERR_INVALID;
+  *len_out = n;
   return DK_OK;
 }
 
