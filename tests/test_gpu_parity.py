@@ -230,3 +230,63 @@ def test_errors_from_gpu_entry_points():
     assert m.pool.length(s) == 10
     m.check_gather(s)
     m.pool.close()
+
+
+@pytest.mark.parametrize("delta", [9, 300])
+def test_growing_scores_exercise_the_lazy_rescale(delta):
+    """Keys whose scores keep outgrowing the reference maximum (by far more than the rescale slack, several
+    times along the prefix, and again inside the new block): the deferred O rescale of the tile kernel and the
+    conditional rescale of the stream kernel must both land on the oracle's result."""
+    sh = SMALL
+    m = Mirror(sh, 1, 8192, seed=23)
+    s = m.acquire()
+    n = 1500
+    rng = np.random.default_rng(23)
+    k = m.draw(n + delta, sh.n_kv_heads)
+    v = m.draw(n + delta, sh.n_kv_heads)
+    q = m.draw(delta, sh.n_q_heads)
+    # a common direction u: keys carry a staircase of it (steps every ~190 positions, plus a final step among the
+    # new tokens), queries a positive multiple, so the row maxima climb by ~15 log2 units per step
+    u = wl.round_to_bf16(rng.standard_normal(sh.head_dim).astype(np.float32))
+    u /= np.linalg.norm(u)
+    step = (np.arange(n + delta) // 190).astype(np.float32)
+    k = wl.round_to_bf16(k + (step * 3.0)[:, None, None] * u[None, None, :])
+    q = wl.round_to_bf16(q + 40.0 * u[None, None, :])
+    m.append([s], [n + delta], k, v)
+    out, lse, _ = m.attend_appended([s], [delta], q, lse=True)
+    ref, ref_lse = m.oracle_appended([s], [delta], q)
+    check_close(out, ref, sh.dtype, "growing scores", scale_abs=True)
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 5e-3 * max(1.0, np.abs(ref_lse).max() / 10)
+    m.pool.close()
+
+
+def test_split_chunks_with_rows_that_see_nothing_of_a_chunk():
+    """A long prefix forces the planner to split the keys; with a diagonal inside the last chunk some rows of a
+    row tile see none of that chunk's keys (their partial is empty) and the merge must ignore it."""
+    sh = SMALL
+    m = Mirror(sh, 1, 1 << 15, seed=29)
+    s = m.acquire()
+    n, delta = 9000, 200
+    m.append([s], [n])
+    kn, vn = m.draw(delta, sh.n_kv_heads), m.draw(delta, sh.n_kv_heads)
+    q = m.draw(delta, sh.n_q_heads)
+    out_s = m.pool.attend([s], [0, delta], to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
+    ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
+    check_close(out_s, ref, sh.dtype, "split, staged")
+    m.pool.close()
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (4, 2), (16, 2), (16, 1), (6, 2)])
+@pytest.mark.parametrize("n,delta", [(300, 3), (700, 100), (40, 260)])
+def test_group_sizes_from_mha_to_sixteen_heads_per_kv_head(hq, hkv, n, delta):
+    """G = Hq/Hkv of 1, 2, 8, 16 (MFMA kernels, rows packed G per token) and 3 (not a power of two: reference kernel)."""
+    sh = wl.Shape(hq, hkv, 128, "bf16")
+    m = Mirror(sh, 2, 4096, granule=32, seed=hq * 100 + hkv * 10 + delta)
+    s = m.acquire()
+    m.append([s], [n])
+    kn, vn = m.draw(delta, hkv), m.draw(delta, hkv)
+    q = m.draw(delta, hq)
+    out = m.pool.attend([s], [0, delta], to_dev(q, "bf16"), sh.scale, to_dev(kn, "bf16"), to_dev(vn, "bf16"))
+    ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
+    check_close(out, ref, "bf16", f"G={hq // hkv}", scale_abs=True)
+    m.pool.close()
