@@ -85,6 +85,7 @@ class Scenario:
                 for s, d in zip(t.slots, t.delta):
                     self._ingest(s, d)
         t = self.turn
+        t.slots = np.asarray(t.slots, dtype=np.int32)  # marshalled once, not per step
         for s, n in zip(t.slots, t.n_past):
             assert self.pool.length(s) == n, (s, self.pool.length(s), n)
         total = sum(t.delta)
@@ -95,7 +96,7 @@ class Scenario:
         self.k_new = torch.randn((total, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
         self.v_new = torch.randn((total, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
         self.out = torch.empty_like(self.q)
-        self.n_accept = list(t.n_accept) if t.staged and t.n_accept else None
+        self.n_accept = np.asarray(t.n_accept, dtype=np.int32) if t.staged and t.n_accept else None
         # size the workspace once, in the state the attend call will see
         if t.staged:
             self.pool.ensure_workspace(t.slots, self.cu, True)

@@ -78,10 +78,17 @@ class DevicePool:
         return self.workspace
 
     def attend(self, slots, cu_delta, q, scale: float, k_new=None, v_new=None, out=None, lse=None):
-        ws = self.ensure_workspace(slots, cu_delta, k_new is not None)
         if out is None:
             out = torch.empty_like(q)
-        dk.delta_attend(self.handle, slots, cu_delta, q, out, scale, k_new, v_new, lse, ws)
+        if self.workspace is None:
+            self.ensure_workspace(slots, cu_delta, k_new is not None)
+        try:  # the library checks the size itself: only a call that outgrows the buffer pays for a size query
+            dk.delta_attend(self.handle, slots, cu_delta, q, out, scale, k_new, v_new, lse, self.workspace)
+        except dk.DeltaKVError as e:
+            if e.name != "WORKSPACE":
+                raise
+            ws = self.ensure_workspace(slots, cu_delta, k_new is not None)
+            dk.delta_attend(self.handle, slots, cu_delta, q, out, scale, k_new, v_new, lse, ws)
         return out
 
     def gather(self, slot: int):
