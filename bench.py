@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (MFMA regime, verify)")
+    ap.add_argument("--drafts", type=int, default=8,
+                    help="c5 only: drafts per slot (Delta = 1 + drafts; 0 is plain decode, 15 fills the stream kernel)")
     ap.add_argument("--vocab", type=int, default=128256, help="vocabulary size of the greedy-verification leg")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB five times "
@@ -167,10 +169,10 @@ class Scenario:
         return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
 
 
-def make_workload(name):
+def make_workload(name, drafts=8):
     from paper_2605_26289_amd import workloads as wl
     if name == "c5":
-        return wl.config5(), -1
+        return wl.config5(k_draft=drafts), -1
     if name == "c4":
         return wl.config4(), -1
     if name == "c4_512":
@@ -321,7 +323,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_per_launch": n, "launches": 5}))
         return
-    w, turn = make_workload(args.workload)
+    w, turn = make_workload(args.workload, args.drafts)
     keep = 0 if args.no_cpu_baseline else min(w.n_slots, 32)
     sc = Scenario(w, turn, keep_host_slots=keep)
     step_s, kern_mean_ms, kern_med_ms = sc.run(args.steps, args.warmup)
