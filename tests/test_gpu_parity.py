@@ -290,3 +290,28 @@ def test_group_sizes_from_mha_to_sixteen_heads_per_kv_head(hq, hkv, n, delta):
     ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
     check_close(out, ref, "bf16", f"G={hq // hkv}", scale_abs=True)
     m.pool.close()
+
+
+@pytest.mark.parametrize("n,delta", [(1000, 9), (777, 200), (130, 70)])
+def test_cells_outside_the_slot_never_reach_the_result(n, delta):
+    """Arena canary: every cell the slots do not own holds NaN.  Ragged tiles, clamped rows, the dummy loads past
+    the end of a key range and aliased prefixes must only ever touch owned cells, or the output turns NaN."""
+    sh = SMALL
+    m = Mirror(sh, 3, 8192, granule=16, seed=31)
+    m.pool.k_arena.fill_(float("nan"))
+    m.pool.v_arena.fill_(float("nan"))
+    a, b = m.acquire(), m.acquire()
+    m.append([a], [n])
+    m.alias(a, b, n - 37)            # b reads a's cells up to an unaligned boundary, then its own
+    m.append([b], [61])
+    kn, vn = m.draw(2 * delta, sh.n_kv_heads), m.draw(2 * delta, sh.n_kv_heads)
+    q = m.draw(2 * delta, sh.n_q_heads)
+    out = m.pool.attend([a, b], [0, delta, 2 * delta], to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
+    assert torch.isfinite(out.float()).all()
+    ref_a, _ = oracle.delta_attend(q[:delta], *m.cache(a), kn[:delta], vn[:delta], sh.scale)
+    ref_b, _ = oracle.delta_attend(q[delta:], *m.cache(b), kn[delta:], vn[delta:], sh.scale)
+    check_close(out, np.concatenate([ref_a, ref_b]), sh.dtype, "canary", scale_abs=True)
+    m.append([a, b], [delta, delta], kn, vn)   # appended mode reads the same cells back
+    out2, _, _ = m.attend_appended([a, b], [delta, delta], q)
+    check_close(out2, np.concatenate([ref_a, ref_b]), sh.dtype, "canary appended", scale_abs=True)
+    m.pool.close()
