@@ -9,9 +9,11 @@ Parity status: every function here is pinned by the CPU test-suite (closed
 forms, brute force, a second independently written full recompute, a library
 attention routine, the paper's printed arithmetic; the verify step by a
 brute-force loop, hand cases and the equivalence with token-by-token
-decoding that the paper calls correctness-preserving).  The absolute output values
-of the five benchmark workloads are printed nowhere in the paper, so those are
-pinned only through these invariants.
+decoding that the paper calls correctness-preserving; the radix cache by
+brute-force longest common prefixes, budget invariants and the paper's cached-token
+counts; the prompt-lookup search by a second formulation).  Parity unpinned: the
+absolute output values of the five benchmark workloads are printed nowhere in the
+paper, so those are pinned only through these invariants.
 """
 from .attention import (  # noqa: F401
     delta_attend,
