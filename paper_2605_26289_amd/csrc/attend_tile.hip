@@ -235,7 +235,6 @@ struct FastStep {
   }
   template <int E>
   __device__ __forceinline__ void expo() {
-    constexpr int mb = (E >> 3) & 1;
     float p = __builtin_amdgcn_exp2f(xe[E & 1]);
     pin(p);
     pe[(E >> 1) & 1][E & 1] = p;
