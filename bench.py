@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--workload", default="c5", choices=["c5", "c4", "c4_512", "c3", "c2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
-    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (MFMA regime, verify)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the secondary measurements (MFMA regime, verify, the other configs)")
     ap.add_argument("--drafts", type=int, default=8,
                     help="c5 only: drafts per slot (Delta = 1 + drafts; 0 is plain decode, 15 fills the stream kernel)")
     ap.add_argument("--vocab", type=int, default=128256, help="vocabulary size of the greedy-verification leg")
@@ -250,6 +251,30 @@ def verify_leg(w, vocab, steps, warmup):
                          "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}}
 
 
+def other_configs(steps, warmup):
+    """Throughput of the remaining workload configs, a few steps each, for the record (no roofline claim for the
+    launch-bound ones).  c3 is reported for its median turn and its final turn."""
+    from paper_2605_26289_amd import workloads as wl
+    import torch
+    out = {}
+    c3 = wl.config3()
+    median_turn = int(np.argsort([t.delta[0] * (t.n_past[0] + 1) for t in c3.turns])[len(c3.turns) // 2])
+    for key, w, turn in (("c1_fp32_single", wl.config1(), -1), ("c2_agent_5turn_final", wl.config2(), -1),
+                         ("c3_coding_median_turn", c3, median_turn), ("c3_coding_final_turn", c3, -1),
+                         ("c4_multi_agent", wl.config4(), -1)):
+        sc = Scenario(w, turn)
+        step_s, kern_ms, _ = sc.run(steps, warmup)
+        fl, by = sc.algorithmic()
+        out[key] = {"new_tokens_per_step": int(sc.total), "cached_tokens": int(sum(sc.turn.n_past)),
+                    "tokens_per_s": round(sc.total / step_s, 1), "ms_per_step": round(step_s * 1e3, 4),
+                    "attend_kernel_ms": round(kern_ms, 4),
+                    "achieved_tflops": round(fl / (kern_ms * 1e-3) / 1e12, 1),
+                    "achieved_gbs": round(by / (kern_ms * 1e-3) / 1e9, 1)}
+        del sc
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(sc, budget_s):
     """Times the fp64 oracle, as it stands, on a bounded sample of the same batch; also checks the GPU rows."""
     import oracle
@@ -341,20 +366,13 @@ def main():
         "algorithmic": {"flops": int(flops), "bytes": int(nbytes)},
         "roofline": roofline_for(args.workload, flops, nbytes, kern_mean_ms),
     }
-    if not args.no_cpu_baseline:
-        base, parity = cpu_baseline(sc, args.cpu_seconds)
-        result["cpu_baseline"] = base
-        result["parity_sample"] = parity
-    else:
-        result["cpu_baseline"] = None
-    del sc
-    torch.cuda.empty_cache()
-
     if not args.no_extra and args.workload == "c5":
+        # The secondary legs run before the CPU leg on purpose: ten seconds of host-only work let the GPU drop
+        # into a low-power state, and the first milliseconds after that are not representative.
         # second regime in the same run: Delta = 512 on every slot of the multi-agent batch (MFMA-bound)
         w2, t2 = make_workload("c4_512")
         sc2 = Scenario(w2, t2)
-        s2, km2, _ = sc2.run(max(5, args.steps // 2), 3)
+        s2, km2, _ = sc2.run(args.steps, max(args.warmup, 10))
         f2, b2 = sc2.algorithmic()
         result["extra"] = {"workload": w2.name + "_delta512", "new_tokens_per_step": int(sc2.total),
                            "tokens_per_s": round(sc2.total / s2, 1), "ms_per_step": round(s2 * 1e3, 4),
@@ -362,6 +380,14 @@ def main():
         del sc2
         torch.cuda.empty_cache()
         result["verify"] = verify_leg(w, args.vocab, args.steps, args.warmup)
+        result["other_configs"] = other_configs(max(5, args.steps // 2), 3)
+    if not args.no_cpu_baseline:
+        base, parity = cpu_baseline(sc, args.cpu_seconds)
+        result["cpu_baseline"] = base
+        result["parity_sample"] = parity
+    else:
+        result["cpu_baseline"] = None
+    del sc
     print(json.dumps(result))
 
 
