@@ -4,7 +4,8 @@ PyTorch is used for allocation and streams only.
 """
 from __future__ import annotations
 
-from typing import Optional, Sequence
+import contextlib
+from typing import Iterator, Optional, Sequence
 
 import torch
 
@@ -54,6 +55,15 @@ class DevicePool:
 
     def release(self, slot: int) -> None:
         dk.seq_release(self.handle, slot)
+
+    @contextlib.contextmanager
+    def sequence(self, region: int = 0, timeout_ms: int = 0) -> Iterator[int]:
+        """Scope guard around acquire / release: the sequence goes back to the pool on every exit path."""
+        slot = self.acquire(region, timeout_ms)
+        try:
+            yield slot
+        finally:
+            self.release(slot)
 
     def length(self, slot: int) -> int:
         return dk.seq_len(self.handle, slot)

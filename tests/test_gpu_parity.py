@@ -315,3 +315,17 @@ def test_cells_outside_the_slot_never_reach_the_result(n, delta):
     out2, _, _ = m.attend_appended([a, b], [delta, delta], q)
     check_close(out2, np.concatenate([ref_a, ref_b]), sh.dtype, "canary appended", scale_abs=True)
     m.pool.close()
+
+
+def test_sequence_guard_returns_the_slot_on_every_exit_path():
+    m = Mirror(SMALL, 1, 1024, granule=16, seed=37)
+    with m.pool.sequence() as s:
+        m.pool.append([s], [0, 5], to_dev(m.draw(5, SMALL.n_kv_heads), "bf16"), to_dev(m.draw(5, SMALL.n_kv_heads), "bf16"))
+        with pytest.raises(dk.DeltaKVError, match="TIMEOUT"):
+            m.pool.acquire()                       # the only slot is taken
+    with pytest.raises(RuntimeError, match="boom"):
+        with m.pool.sequence() as s2:
+            assert s2 == s and m.pool.length(s2) == 0  # released and recycled empty
+            raise RuntimeError("boom")
+    assert m.pool.acquire() == s                   # the exception path released it too
+    m.pool.close()
