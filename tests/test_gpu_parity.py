@@ -329,3 +329,27 @@ def test_sequence_guard_returns_the_slot_on_every_exit_path():
             raise RuntimeError("boom")
     assert m.pool.acquire() == s                   # the exception path released it too
     m.pool.close()
+
+
+def test_attend_timing_ring_keeps_the_last_calls_in_order():
+    """The per-call kernel timer: n recorded calls give n positive durations, oldest first, and the
+    ring keeps only the most recent ones; a larger batch takes longer than a tiny one."""
+    m = Mirror(SMALL, 2, 16384, seed=41)
+    a, b = m.acquire(), m.acquire()
+    m.append([a, b], [6000, 40])
+    h = m.pool.handle
+    with pytest.raises(dk.DeltaKVError):
+        dk.last_attend_ms(h)  # recording is off: nothing to report
+    dk.set_attend_timing(h, 3)
+    q_big, q_small = m.draw(512, SMALL.n_q_heads), m.draw(1, SMALL.n_q_heads)
+    m.attend_appended([b], [1], q_small)  # warm-up, will be pushed out of the ring
+    for slots, deltas, q in (([a], [512], q_big), ([b], [1], q_small), ([a], [512], q_big)):
+        m.attend_appended(slots, deltas, q)
+    ms = dk.attend_times(h)
+    assert ms.shape == (3,) and (ms > 0).all()
+    assert ms[0] > ms[1] and ms[2] > ms[1]
+    assert dk.last_attend_ms(h) == pytest.approx(float(ms[2]))
+    assert dk.attend_times(h, cap=2).tolist() == pytest.approx(ms[1:].tolist())
+    dk.set_attend_timing(h, 0)
+    assert dk.attend_times(h).size == 0
+    m.pool.close()

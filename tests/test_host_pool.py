@@ -34,6 +34,13 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(dk.SIGNATURES)
 
 
+def test_every_status_code_has_its_own_message():
+    codes = [0] + list(range(-1, -9, -1))
+    texts = [dk.strerror(c) for c in codes]
+    assert all(t and "unknown" not in t.lower() for t in texts) and len(set(texts)) == len(texts)
+    assert "unknown" in dk.strerror(-99).lower() or dk.strerror(-99) not in texts
+
+
 def test_create_rejects_bad_descriptions():
     def rc(**kw):
         base = dict(n_slots=2, n_session_slots=0, arena_cells=512, granule_cells=16, n_q_heads=8, n_kv_heads=2,
