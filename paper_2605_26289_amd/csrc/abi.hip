@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -153,6 +154,15 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
   c.stream_target = env_int("DELTAKV_STREAM_TARGET", 256 / desc->n_kv_heads);
   c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 1024);
   c.stream_min_chunk = env_int("DELTAKV_STREAM_MIN_CHUNK", 512);
+  c.stream_chains = env_int("DELTAKV_STREAM_CHAINS", 256);
+  c.stream_item_cost = env_int("DELTAKV_STREAM_ITEM_COST", 512);
+  for (float& x : c.xcd_speed) x = 1.f;
+  if (const char* v = std::getenv("DELTAKV_XCD_SPEEDS")) {  // eight comma-separated relative rates
+    float f[8];
+    if (std::sscanf(v, "%f,%f,%f,%f,%f,%f,%f,%f", &f[0], &f[1], &f[2], &f[3], &f[4], &f[5], &f[6], &f[7]) == 8)
+      for (int x = 0; x < 8; ++x)
+        if (f[x] > 0.f) c.xcd_speed[x] = f[x];
+  }
   if (c.tile_target < 1) c.tile_target = 1;
   if (c.stream_target < 1) c.stream_target = 1;
   *pool_out = p;
@@ -303,6 +313,7 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   put(plan.off_segs, plan.segs.data(), plan.segs.size() * sizeof(DkSeg));
   put(plan.off_tile, plan.tile_items.data(), plan.tile_items.size() * sizeof(DkItem));
   put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
+  put(plan.off_links, plan.stream_links.data(), plan.stream_links.size() * sizeof(int32_t));
   put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
   rc = pool->upload(s, workspace, plan.blob_bytes, st);
   if (rc != DK_OK) return rc;
@@ -335,7 +346,8 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   } else {
     e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (int32_t)plan.tile_items.size(), st);
     if (e != hipSuccess) return pool->hip_fail(e);
-    e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (int32_t)plan.stream_items.size(), st);
+    e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (const int32_t*)(ws + plan.off_links),
+                                 plan.stream_chains, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
   if (timing) {

@@ -153,14 +153,17 @@ constexpr int STREAM_WAVE_BYTES = 2 * STREAM_STAGE_BYTES;      // 32 KiB
 constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages / the merge buffer
 constexpr int STREAM_LDS_BYTES = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
 
-__global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c) {
+__global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c, const int32_t* links, int n_chains) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int MB = 2;
-  const int g = blockIdx.x % c.n_kv_heads;
-  const DkItem it = load_desc(c.items, blockIdx.x / c.n_kv_heads);
-  const DkEntry e = load_desc(c.entries, it.entry);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // The workgroup walks its chain of units (item, KV head); the planner balanced the chains against
+  // each other.
+  for (int unit = load_desc(links, blockIdx.x); unit >= 0;) {
+  const int g = unit % c.n_kv_heads;
+  const DkItem it = load_desc(c.items, unit / c.n_kv_heads);
+  const DkEntry e = load_desc(c.entries, it.entry);
   const int last_row = it.row0 + it.nrows - 1;
   const int min_limit = e.n + (it.row0 >> c.gshift);
 
@@ -273,13 +276,17 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c) {
   }
   store_block<MB>(c, e, it, g, 0, lane, db, acc, ll);
   if (wave == 0) store_ml<MB>(c, e, it, g, 0, lane, mm, ll);
+  unit = load_desc(links, n_chains + unit);
+  if (unit >= 0) __syncthreads();  // the merge buffer has been read everywhere: it may become K/V stages again
+  }
 }
 
 }  // namespace mfma
 
-hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream) {
+hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
+                                hipStream_t stream) {
   using namespace mfma;
-  if (n_items <= 0) return hipSuccess;
+  if (n_chains <= 0) return hipSuccess;
   if (a.arena.head_dim != D || a.arena.dtype != 1) return hipErrorInvalidValue;
   static bool attr_done = false;
   if (!attr_done) {
@@ -289,7 +296,7 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, int32_
     attr_done = true;
   }
   const Ctx c = make_ctx(a, items);
-  attend_stream_kernel<<<dim3((unsigned)n_items * a.arena.n_kv_heads), 256, STREAM_LDS_BYTES, stream>>>(c);
+  attend_stream_kernel<<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
   return hipGetLastError();
 }
 

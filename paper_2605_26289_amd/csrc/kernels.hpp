@@ -41,7 +41,10 @@ struct AttendArgs {
 hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream);
 // bf16 MFMA kernels (head_dim 128).
 hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
-hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
+// Unit u = item u / n_kv_heads for KV head u % n_kv_heads.  Workgroup w walks the chain links[w],
+// links[n_chains + that unit], ... until a link is negative.
+hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
+                                hipStream_t stream);
 hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, hipStream_t stream);
 
 // Greedy verification (argmax per logits row, accepted-draft count and next token per slot).

@@ -1,6 +1,8 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <functional>
+#include <queue>
 
 namespace dk {
 
@@ -83,6 +85,51 @@ void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t targe
   }
   for (const Keyed& k : keyed) items->push_back(k.it);
 }
+
+// The streaming kernel runs one workgroup per compute unit, and a workgroup walks a chain of units
+// (item, KV head).  Its workgroups share no K/V rows, so a unit may run on any XCD.  The units arrive
+// longest first and each joins the chain that is free first (longest-processing-time rule on machines of
+// unequal speed: workgroup w runs on XCD w % 8, and the XCDs do not stream from HBM equally fast; among
+// idle chains the faster ones are served first, so they get the longest units), so that all compute
+// units finish together whatever the mix of context lengths.  With very many small units, runs of
+// consecutive units are handed out as one block to keep the planning time down.
+void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::vector<int32_t>* links,
+                 int32_t* n_chains) {
+  const int64_t n_units = (int64_t)items.size() * cfg.n_kv_heads;
+  const int32_t chains = (int32_t)std::min<int64_t>(n_units, std::max(cfg.stream_chains, 1));
+  *n_chains = chains;
+  links->assign((size_t)(chains + n_units), -1);
+  int32_t* head = links->data();
+  int32_t* next = links->data() + chains;
+  if (n_units == chains) {  // one unit each: nothing to balance
+    for (int32_t c = 0; c < chains; ++c) head[c] = c;
+    return;
+  }
+  double inv_speed[8];
+  for (int x = 0; x < 8; ++x) inv_speed[x] = 1.0 / (cfg.xcd_speed[x] > 0.f ? cfg.xcd_speed[x] : 1.f);
+  typedef std::pair<double, int32_t> Free;  // (time at which the chain is free, chain)
+  std::vector<Free> heap((size_t)chains);
+  for (int32_t c = 0; c < chains; ++c) heap[c] = {1e-6 * inv_speed[c & 7], c};
+  const auto later = [](const Free& a, const Free& b) { return a > b; };
+  std::make_heap(heap.begin(), heap.end(), later);
+  std::vector<int32_t> tail((size_t)chains, -1);
+  const int64_t per_block = (n_units + 8 * (int64_t)chains - 1) / (8 * (int64_t)chains);
+  for (int64_t u0 = 0; u0 < n_units; u0 += per_block) {
+    const int64_t u1 = std::min(n_units, u0 + per_block);
+    std::pop_heap(heap.begin(), heap.end(), later);
+    Free& f = heap.back();
+    const int32_t c = f.second;
+    int64_t cost = 0;
+    for (int64_t u = u0; u < u1; ++u) {
+      const DkItem& it = items[(size_t)(u / cfg.n_kv_heads)];
+      cost += (int64_t)(it.kv_hi - it.kv_lo) + cfg.stream_item_cost;
+      if (tail[c] < 0) head[c] = (int32_t)u; else next[tail[c]] = (int32_t)u;
+      tail[c] = (int32_t)u;
+    }
+    f.first += (double)cost * inv_speed[c & 7];
+    std::push_heap(heap.begin(), heap.end(), later);
+  }
+}
 }  // namespace
 
 int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
@@ -129,6 +176,7 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
             &p->part_rows);
   cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, &p->stream_items,
             &p->merges, &p->part_rows);
+  chain_units(p->stream_items, cfg, &p->stream_links, &p->stream_chains);
 
   size_t off = 0;
   p->off_entries = off;
@@ -139,6 +187,8 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
   off = align_up(off + p->tile_items.size() * sizeof(DkItem), 256);
   p->off_stream = off;
   off = align_up(off + p->stream_items.size() * sizeof(DkItem), 256);
+  p->off_links = off;
+  off = align_up(off + p->stream_links.size() * sizeof(int32_t), 256);
   p->off_merges = off;
   off = align_up(off + p->merges.size() * sizeof(DkMerge), 256);
   p->blob_bytes = off;

@@ -20,6 +20,9 @@ struct PlanConfig {
   int32_t tile_target;    // aimed number of items per KV head, tile kernel
   int32_t stream_target;  // same, streaming kernel
   int32_t tile_min_chunk, stream_min_chunk;  // smallest key range worth its own item
+  int32_t stream_chains;     // workgroups of the streaming kernel: one per compute unit
+  int32_t stream_item_cost;  // fixed cost of an item in the chain balance, in keys
+  float xcd_speed[8];        // relative K/V streaming rate of the XCD that workgroup w lands on (w % 8)
 };
 
 struct AttendPlan {
@@ -29,7 +32,11 @@ struct AttendPlan {
   std::vector<DkMerge> merges;
   int64_t total_tokens = 0;
   int64_t part_rows = 0;
-  size_t off_entries = 0, off_segs = 0, off_tile = 0, off_stream = 0, off_merges = 0;
+  // Streaming kernel: unit u = item u / n_kv_heads for KV head u % n_kv_heads.  Workgroup w walks the
+  // chain stream_links[w], stream_links[n_chains + that unit], ... until a link is negative.
+  std::vector<int32_t> stream_links;
+  int32_t stream_chains = 0;
+  size_t off_entries = 0, off_segs = 0, off_tile = 0, off_stream = 0, off_links = 0, off_merges = 0;
   size_t blob_bytes = 0;   // descriptors
   size_t off_parts = 0;    // fp32 partial rows, each (head_dim + 2) floats per KV head
   size_t total_bytes = 0;  // whole workspace

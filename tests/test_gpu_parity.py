@@ -353,3 +353,24 @@ def test_attend_timing_ring_keeps_the_last_calls_in_order():
     dk.set_attend_timing(h, 0)
     assert dk.attend_times(h).size == 0
     m.pool.close()
+
+
+@pytest.mark.parametrize("n_slots,n_hi", [(300, 400), (1400, 90)])
+def test_many_small_slots_walk_chains_of_units(n_slots, n_hi):
+    """More (slot, KV head) units than compute units: each streaming workgroup walks a chain of them (600
+    units: two or three each; 2800 units: handed out in blocks).  Every slot's rows must still come out right."""
+    rng = np.random.default_rng(n_slots)
+    m = Mirror(SMALL, n_slots, n_slots * (n_hi + 8) + 4096, granule=16, seed=n_slots)
+    slots = [m.acquire() for _ in range(n_slots)]
+    hist = rng.integers(0, n_hi + 1, size=n_slots).tolist()
+    live = [s for s, h in zip(slots, hist) if h]
+    m.append(live, [h for h in hist if h])
+    deltas = rng.integers(0, 4, size=n_slots).tolist()  # decode, short verify steps and idle slots mixed
+    deltas[0], deltas[-1] = 3, 1
+    q = m.draw(sum(deltas), SMALL.n_q_heads)
+    m.append(slots, deltas)
+    out, lse, _ = m.attend_appended(slots, deltas, q, lse=True)
+    ref, ref_lse = m.oracle_appended(slots, deltas, q)
+    check_close(out, ref, SMALL.dtype, f"{n_slots} slots")
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    m.pool.close()

@@ -1,0 +1,26 @@
+"""The attend planner's work decomposition (host C++, no GPU): compiles the planner together with a checker
+and runs it.  Every (row, key) pair must be covered by exactly one work item, rows whose keys were split must
+have a merge record, and the chains the streaming kernel's workgroups walk must hold every (item, KV head)
+unit exactly once and finish together, also when the XCDs differ in speed."""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2605_26289_amd", "csrc")
+
+
+def test_plan_covers_every_row_and_key_once_and_balances_chains(tmp_path):
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no host C++ compiler")
+    exe = str(tmp_path / "plan_check")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-pthread", os.path.join(ROOT, "tests", "plan_check.cpp"),
+           os.path.join(CSRC, "plan.cpp"), os.path.join(CSRC, "pool.cpp"), "-o", exe]
+    built = subprocess.run(cmd, capture_output=True, text=True)
+    assert built.returncode == 0, built.stderr[-3000:]
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, (run.stdout[-3000:], run.stderr[-2000:])
+    assert "failures 0" in run.stdout
