@@ -213,6 +213,11 @@ int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const 
   int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst);
   if (rc != DK_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
+  if (total <= dk::KV_INLINE_MAX_TOKENS) {
+    hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
+                                                (int32_t)total, k_new, v_new, st);
+    return e == hipSuccess ? DK_OK : pool->hip_fail(e);
+  }
   const int64_t per_launch = pool->desc.dev_meta_bytes / (int64_t)sizeof(int32_t);
   for (int64_t base = 0; base < total; base += per_launch) {
     const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);

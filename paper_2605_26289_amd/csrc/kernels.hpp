@@ -22,6 +22,12 @@ hipError_t launch_kv_scatter(const ArenaView& a, void* k_arena, void* v_arena, c
 hipError_t launch_kv_gather(const ArenaView& a, const int32_t* cell_of_dev, int64_t tok_base, int32_t n_tok,
                             void* k_out, void* v_out, hipStream_t stream);
 
+// Appends of at most this many tokens carry their destination cells in the kernel arguments (host table,
+// nothing is uploaded first).
+constexpr int32_t KV_INLINE_MAX_TOKENS = 896;
+hipError_t launch_kv_scatter_inline(const ArenaView& a, void* k_arena, void* v_arena, const int64_t* cell_of_host,
+                                    int32_t n_tok, const void* k_new, const void* v_new, hipStream_t stream);
+
 struct AttendArgs {
   ArenaView arena;
   const DkEntry* entries;

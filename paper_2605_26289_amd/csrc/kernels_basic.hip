@@ -35,6 +35,54 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(uint4* __restrict__ k_aren
 
 static int32_t row_vecs(const ArenaView& a) { return a.head_dim * (a.dtype == 0 ? 4 : 2) / 16; }
 
+// Short appends (a verify step, a tool result of a few hundred tokens): the destination cells travel
+// inside the kernel arguments, so no table has to be copied to the device before the launch -- on a
+// short turn that copy and the dependency bubble after it cost more than the append itself.
+struct InlineCells {
+  int32_t cell[KV_INLINE_MAX_TOKENS];
+};
+static_assert(sizeof(InlineCells) + 128 <= 4096, "kernel arguments are limited to 4 KiB");
+
+__global__ __launch_bounds__(256) void kv_scatter_inline_kernel(InlineCells cells, uint4* __restrict__ k_arena,
+                                                                uint4* __restrict__ v_arena,
+                                                                const uint4* __restrict__ k_tok,
+                                                                const uint4* __restrict__ v_tok, int32_t n_tok,
+                                                                int32_t n_kv_heads, int32_t row_vec,
+                                                                int64_t arena_cells) {
+  // `cells` is the first argument: it starts the kernel-argument segment.  Reading it through the
+  // segment pointer keeps the (lane-dependent) index from forcing a private copy of the whole table.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const_i32_ptr cell_of = (const_i32_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+  (void)cells;
+  const int32_t per_tok = n_kv_heads * row_vec;
+  const int32_t idx = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (idx >= per_tok * n_tok) return;
+  const int32_t t = idx / per_tok;
+  const int32_t rem = idx - t * per_tok;
+  const int32_t g = rem / row_vec;
+  const int32_t c = rem - g * row_vec;
+  const int64_t cell = cell_of[t];
+  if (cell < 0) return;
+  const int64_t tok_off = ((int64_t)t * n_kv_heads + g) * row_vec + c;
+  const int64_t arena_off = ((int64_t)g * arena_cells + cell) * row_vec + c;
+  if (blockIdx.y) v_arena[arena_off] = v_tok[tok_off];
+  else k_arena[arena_off] = k_tok[tok_off];
+}
+
+hipError_t launch_kv_scatter_inline(const ArenaView& a, void* k_arena, void* v_arena, const int64_t* cell_of_host,
+                                    int32_t n_tok, const void* k_new, const void* v_new, hipStream_t stream) {
+  if (n_tok <= 0) return hipSuccess;
+  if (n_tok > KV_INLINE_MAX_TOKENS) return hipErrorInvalidValue;
+  InlineCells cells{};
+  for (int32_t t = 0; t < n_tok; ++t) cells.cell[t] = (int32_t)cell_of_host[t];
+  const int32_t rv = row_vecs(a);
+  const int64_t work = (int64_t)n_tok * a.n_kv_heads * rv;
+  dim3 grid((unsigned)((work + 255) / 256), 2);
+  kv_scatter_inline_kernel<<<grid, 256, 0, stream>>>(cells, (uint4*)k_arena, (uint4*)v_arena, (const uint4*)k_new,
+                                                     (const uint4*)v_new, n_tok, a.n_kv_heads, rv, a.arena_cells);
+  return hipGetLastError();
+}
+
 hipError_t launch_kv_scatter(const ArenaView& a, void* k_arena, void* v_arena, const int32_t* cell_of_dev,
                              int64_t tok_base, int32_t n_tok, const void* k_new, const void* v_new,
                              hipStream_t stream) {
