@@ -68,3 +68,32 @@ def test_config4_full_size_delta512_sampled_rows():
 
 def test_config3_full_size_final_turn_sampled_rows():
     _sampled_parity("c3", keep=1, rows_per_slot=16)
+
+
+def test_context_cap_chunk_ceiling_and_decode_sampled_rows():
+    """The largest shapes the paper's deployment allows (Sec. 4.1: 32 768-token context; Sec. 3.2: prefill chunks
+    of at most 4096 tokens): one slot takes a 4096-token chunk that fills its context to the cap, another decodes
+    its last token at the cap, in one call.  Sampled rows against the oracle."""
+    from gpu_util import Mirror
+    from paper_2605_26289_amd import workloads as wl
+
+    cap, chunk = 32768, 4096
+    m = Mirror(wl.PRODUCTION, 2, 2 * cap + 1024, seed=77)
+    a, b = m.acquire(), m.acquire()
+    m.append([a], [cap - chunk])
+    m.append([b], [cap - 1])
+    deltas = [chunk, 1]
+    q = m.draw(chunk + 1, wl.PRODUCTION.n_q_heads)
+    m.append([a, b], deltas)
+    assert m.pool.length(a) == cap and m.pool.length(b) == cap
+    out, lse, _ = m.attend_appended([a, b], deltas, q, lse=True)
+    rows = [sorted({0, 1, 63, 64, 255, 256, 1000, 2047, 2048, 4031, 4094, 4095}), [0]]
+    ref, ref_lse = m.oracle_appended([a, b], deltas, q, rows_per_seq=rows)
+    pick = np.array(rows[0] + [chunk])
+    gpu = out.float().cpu().numpy()[pick]
+    assert np.isfinite(out.float().cpu().numpy()).all()
+    diff = np.abs(gpu - ref[pick])
+    rms = np.sqrt((ref[pick] ** 2).mean(axis=-1, keepdims=True))
+    assert diff.max() <= ABS_TOL and (diff / np.maximum(np.abs(ref[pick]), rms)).max() <= REL_TOL
+    assert np.abs(lse.cpu().numpy()[pick] - ref_lse[pick]).max() < 2e-3
+    m.pool.close()
