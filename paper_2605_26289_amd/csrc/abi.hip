@@ -361,7 +361,9 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
     ++pool->ev_calls;
   }
   if (cfg.use_mfma) {
-    e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), st);
+    int32_t max_rows = 0;
+    for (const DkMerge& mg : plan.merges) max_rows = std::max(max_rows, mg.nrows);
+    e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), max_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
   return DK_OK;

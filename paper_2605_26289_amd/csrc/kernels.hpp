@@ -51,7 +51,9 @@ hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t 
 // links[n_chains + that unit], ... until a link is negative.
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
                                 hipStream_t stream);
-hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, hipStream_t stream);
+// max_rows: the largest DkMerge::nrows among them (sizes the grid).
+hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, int32_t max_rows,
+                               hipStream_t stream);
 
 // Greedy verification (argmax per logits row, accepted-draft count and next token per slot).
 int64_t verify_workspace_bytes(int32_t total_rows, int64_t vocab, int32_t dtype);

@@ -249,7 +249,9 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream) {
 // ---------------------------------------------------------------------------------------------
 // Merge of split key ranges.  Each split left, per (row, KV head), D unnormalised fp32 sums, its
 // running maximum m (log2 units) and its weight sum l.  O = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
-// Block = 4 wavefronts, one row each per step; lanes cover D.
+// One wavefront per (row, KV head): first every lane takes one split and fetches its (m, l), which gives
+// the common maximum, the weights and the weight sum in one round trip; then the lanes cover D and add
+// the splits' sums, four independent loads in flight at a time.
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void attend_merge_kernel(const DkMerge* __restrict__ merges,
@@ -258,50 +260,73 @@ __global__ __launch_bounds__(256) void attend_merge_kernel(const DkMerge* __rest
                                                            float* __restrict__ lse, int32_t n_q_heads,
                                                            int32_t n_kv_heads) {
   constexpr int PS = D + 2;
-  constexpr int PER = D / 64;
+  static_assert(D == 128, "two floats per lane");
   const DkMerge mg = merges[blockIdx.x];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int r = blockIdx.z * 4 + wave;
+  if (r >= mg.nrows) return;
   const DkEntry e = entries[mg.entry];
   const int g = blockIdx.y;
   const int group = n_q_heads / n_kv_heads;
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  for (int r = blockIdx.z * 4 + wave; r < mg.nrows; r += gridDim.z * 4) {
-    float mmax = -INFINITY;
-    for (int s = 0; s < mg.nsplit; ++s) {
-      const float* p = parts + ((int64_t)(mg.part_row0 + s * mg.nrows + r) * n_kv_heads + g) * PS;
-      mmax = fmaxf(mmax, p[D]);
+  const float* p0 = parts + ((int64_t)(mg.part_row0 + r) * n_kv_heads + g) * PS;
+  const int64_t stride = (int64_t)mg.nrows * n_kv_heads * PS;  // from one split of the row to the next
+
+  float mmax = -INFINITY;
+  for (int s = lane; s < mg.nsplit; s += 64) mmax = fmaxf(mmax, p0[s * stride + D]);
+#pragma unroll
+  for (int off = 32; off; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off));
+
+  float2 acc = {0.f, 0.f};
+  float lsum = 0.f;
+  for (int s0 = 0; s0 < mg.nsplit; s0 += 64) {
+    const int mine = s0 + lane;
+    float w_mine = 0.f;
+    if (mine < mg.nsplit) {
+      const float ms = p0[mine * stride + D];  // second touch: served from cache
+      w_mine = (ms == -INFINITY) ? 0.f : exp2f(ms - mmax);
+      lsum += w_mine * p0[mine * stride + D + 1];
     }
-    float acc[PER];
-#pragma unroll
-    for (int c = 0; c < PER; ++c) acc[c] = 0.f;
-    float lsum = 0.f;
-    for (int s = 0; s < mg.nsplit; ++s) {
-      const float* p = parts + ((int64_t)(mg.part_row0 + s * mg.nrows + r) * n_kv_heads + g) * PS;
-      const float ms = p[D];
-      const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - mmax);
-      lsum += w * p[D + 1];
-#pragma unroll
-      for (int c = 0; c < PER; ++c) acc[c] += w * p[lane * PER + c];
+    const int cnt = min(64, mg.nsplit - s0);
+    const float* p = p0 + s0 * stride + lane * 2;
+    int s = 0;
+    for (; s + 4 <= cnt; s += 4) {
+      const float2 v0 = *(const float2*)(p + (s + 0) * stride);
+      const float2 v1 = *(const float2*)(p + (s + 1) * stride);
+      const float2 v2 = *(const float2*)(p + (s + 2) * stride);
+      const float2 v3 = *(const float2*)(p + (s + 3) * stride);
+      const float w0 = __shfl(w_mine, s + 0), w1 = __shfl(w_mine, s + 1);
+      const float w2 = __shfl(w_mine, s + 2), w3 = __shfl(w_mine, s + 3);
+      acc.x += w0 * v0.x + w1 * v1.x + w2 * v2.x + w3 * v3.x;
+      acc.y += w0 * v0.y + w1 * v1.y + w2 * v2.y + w3 * v3.y;
     }
-    const int row = mg.row0 + r;
-    const int tok = e.tok0 + row / group;
-    const int h = g * group + row % group;
-    const float inv = 1.f / lsum;
-    __bf16* o = out + ((int64_t)tok * n_q_heads + h) * D + lane * PER;
-#pragma unroll
-    for (int c = 0; c < PER; ++c) o[c] = (__bf16)(acc[c] * inv);
-    if (lse && lane == 0) lse[(int64_t)tok * n_q_heads + h] = (mmax + log2f(lsum)) * 0.6931471805599453f;
+    for (; s < cnt; ++s) {
+      const float2 v = *(const float2*)(p + s * stride);
+      const float w = __shfl(w_mine, s);
+      acc.x += w * v.x;
+      acc.y += w * v.y;
+    }
   }
+#pragma unroll
+  for (int off = 32; off; off >>= 1) lsum += __shfl_xor(lsum, off);
+
+  const int row = mg.row0 + r;
+  const int tok = e.tok0 + row / group;
+  const int h = g * group + row % group;
+  const float inv = 1.f / lsum;
+  __bf16* o = out + ((int64_t)tok * n_q_heads + h) * D + lane * 2;
+  o[0] = (__bf16)(acc.x * inv);
+  o[1] = (__bf16)(acc.y * inv);
+  if (lse && lane == 0) lse[(int64_t)tok * n_q_heads + h] = (mmax + log2f(lsum)) * 0.6931471805599453f;
 }
 
-hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, hipStream_t stream) {
+hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, int32_t max_rows,
+                               hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
-  dim3 grid((unsigned)n_merges, (unsigned)a.arena.n_kv_heads, 8);
-  if (a.arena.head_dim == 128)
-    attend_merge_kernel<128><<<grid, 256, 0, stream>>>(merges, a.entries, a.parts, (__bf16*)a.out, a.lse,
-                                                       a.arena.n_q_heads, a.arena.n_kv_heads);
-  else
-    return hipErrorInvalidValue;
+  if (a.arena.head_dim != 128 || max_rows <= 0) return hipErrorInvalidValue;
+  dim3 grid((unsigned)n_merges, (unsigned)a.arena.n_kv_heads, (unsigned)((max_rows + 3) / 4));
+  attend_merge_kernel<128><<<grid, 256, 0, stream>>>(merges, a.entries, a.parts, (__bf16*)a.out, a.lse,
+                                                     a.arena.n_q_heads, a.arena.n_kv_heads);
   return hipGetLastError();
 }
 
