@@ -152,7 +152,8 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
   // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
   // item costs a ramp-up, a partial write and merge work, and longest-first dispatch balances the rest
   c.stream_target = env_int("DELTAKV_STREAM_TARGET", 256 / desc->n_kv_heads);
-  c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 1024);
+  c.tile_wave_slots = env_int("DELTAKV_TILE_WAVE_SLOTS", std::max(1, 256 / desc->n_kv_heads));
+  c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 128);
   c.stream_min_chunk = env_int("DELTAKV_STREAM_MIN_CHUNK", 512);
   c.stream_chains = env_int("DELTAKV_STREAM_CHAINS", 256);
   c.stream_item_cost = env_int("DELTAKV_STREAM_ITEM_COST", 512);

@@ -19,12 +19,46 @@ struct RowTile {
 // read the same K/V tiles, so they are made neighbours in launch order (`group` = true) and, running
 // at the same time on the XCD of their KV head, fetch each tile from HBM once and from L2 after that.
 void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk, bool group,
-               std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
+               int32_t wave_slots, std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
   if (tiles.empty()) return;
   int64_t total = 0;
-  for (const RowTile& t : tiles) total += t.kv_hi;
+  int32_t longest = 0;
+  for (const RowTile& t : tiles) {
+    total += t.kv_hi;
+    longest = std::max(longest, t.kv_hi);
+  }
   int64_t chunk = std::max<int64_t>(min_chunk, (total + target - 1) / target);
   chunk = (chunk + kv_tile - 1) / kv_tile * kv_tile;
+  if (group && wave_slots > 0) {
+    // Tile kernel: pick the chunk length by a small cost model instead.  `wave_slots` workgroups of a KV
+    // head run at a time, so n items take ceil(n / wave_slots) rounds; a round lasts as long as an item,
+    // (work / n) key tiles plus the fixed cost of a workgroup (descriptor and Q loads, pipeline ramp,
+    // output store: about 12 us, or seven key tiles).  Splitting finer shortens the rounds but adds
+    // rounds and fixed costs; what matters most is landing on a whole number of rounds.
+    const double fixed = 7.0;
+    const double work = (double)total / kv_tile;
+    double best = 0;
+    int64_t best_chunk = 0;
+    for (int32_t k = 1; k <= 512; k += (k < 16 ? 1 : k < 64 ? 4 : 16)) {
+      int64_t cand = ((longest + k - 1) / k + kv_tile - 1) / kv_tile * kv_tile;
+      if (cand < min_chunk) break;
+      int64_t n = 0;
+      for (size_t b = 0; b < tiles.size();) {
+        size_t e = b;
+        int32_t hi_max = 0;
+        while (e < tiles.size() && tiles[e].entry == tiles[b].entry) hi_max = std::max(hi_max, tiles[e++].kv_hi);
+        n += (int64_t)(e - b) * ((hi_max + cand - 1) / cand);
+        b = e;
+      }
+      const double rounds = (double)((n + wave_slots - 1) / wave_slots);
+      const double cost = rounds * (work / (double)n + fixed);
+      if (best_chunk == 0 || cost < best * 0.999) {
+        best = cost;
+        best_chunk = cand;
+      }
+    }
+    if (best_chunk) chunk = best_chunk;
+  }
 
   struct Keyed {
     DkItem it;
@@ -172,9 +206,9 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
       }
     }
   }
-  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, &p->tile_items, &p->merges,
-            &p->part_rows);
-  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, &p->stream_items,
+  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, &p->tile_items,
+            &p->merges, &p->part_rows);
+  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, &p->stream_items,
             &p->merges, &p->part_rows);
   chain_units(p->stream_items, cfg, &p->stream_links, &p->stream_chains);
 

@@ -17,7 +17,8 @@ struct PlanConfig {
   int32_t tile_rows;      // packed query rows per workgroup of the tile kernel
   int32_t stream_rows;    // max packed rows handled by the streaming (small-Delta) kernel
   int32_t kv_tile;        // keys per inner step; split boundaries are multiples of it
-  int32_t tile_target;    // aimed number of items per KV head, tile kernel
+  int32_t tile_target;    // aimed number of items per KV head, tile kernel (when tile_wave_slots is 0)
+  int32_t tile_wave_slots;  // tile-kernel workgroups of one KV head that run at a time (its share of the CUs)
   int32_t stream_target;  // same, streaming kernel
   int32_t tile_min_chunk, stream_min_chunk;  // smallest key range worth its own item
   int32_t stream_chains;     // workgroups of the streaming kernel: one per compute unit

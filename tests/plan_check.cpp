@@ -30,8 +30,9 @@ static dk::PlanConfig config(int hq, int hkv) {
   c.stream_rows = 64;
   c.kv_tile = 64;
   c.tile_target = 3 * 256 / hkv;
+  c.tile_wave_slots = 256 / hkv;
   c.stream_target = 256 / hkv;
-  c.tile_min_chunk = 1024;
+  c.tile_min_chunk = 128;
   c.stream_min_chunk = 512;
   c.stream_chains = 256;
   c.stream_item_cost = 512;
