@@ -158,6 +158,8 @@ __device__ __forceinline__ bf16x8 read_v_frag(const char* v_lds, uint32_t lane_o
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Issues the loads of a wavefront's Q fragments; wait_q() below is where they must have arrived.  What is
+// put between the two (finding the first K/V tiles and requesting them) overlaps with the Q round trip.
 template <int MB>
 __device__ __forceinline__ void load_q(const Ctx& c, const DkEntry& e, int g, int row_base, int last_row, int lane,
                                        bf16x8 (&qf)[MB][8], int (&limit)[MB]) {
@@ -172,8 +174,13 @@ __device__ __forceinline__ void load_q(const Ctx& c, const DkEntry& e, int g, in
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[mb][ks] = *(const bf16x8*)(qp + ks * 16);
   }
-  // Make the compiler wait for Q here, once, instead of at first use inside the key loop, where its
-  // vmcnt(0) would also drain the K/V tiles that are meant to stay in flight.
+}
+
+// Makes the compiler wait for Q here, once, instead of at first use inside the key loop, where its
+// vmcnt(0) would also drain the K/V tiles that are meant to stay in flight.  (The wait it emits here is a
+// vmcnt(0) as well: K/V tiles requested before this point land before the key loop starts.)
+template <int MB>
+__device__ __forceinline__ void wait_q(const bf16x8 (&qf)[MB][8]) {
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll

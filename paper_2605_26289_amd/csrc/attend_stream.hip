@@ -206,6 +206,7 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c, const int3
   bool have1 = have0 && cur.next(c, g, STREAM_KT, t1);
   if (have0) issue(t0, 0);
   if (have1) issue(t1, 1);
+  wait_q<MB>(qf);
   int stage = 0;
   TileFrags fr;
   while (have0) {

@@ -375,12 +375,7 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
 
   bf16x8 qf[MB][8];
   int limit[MB];
-  load_q<MB>(c, e, g, wave_row0, last_row, lane, qf, limit);
-  // From here on Q is only ever an AGPR operand: give it its home there, once, instead of a copy per use.
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[mb][ks]));
+  load_q<MB>(c, e, g, wave_row0, last_row, lane, qf, limit);  // waited for below, after the first K/V requests
 
   WaveState st;
 #pragma unroll
@@ -451,6 +446,13 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   if (offsets_stale()) refresh_offsets();
   aim(1, 1);
   issue_all();
+
+  wait_q<MB>(qf);
+  // From here on Q is only ever an AGPR operand: give it its home there, once, instead of a copy per use.
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[mb][ks]));
 
   f32x16 sa[2][MB], sb[2][MB];
   u32x4 pa[MB][4], pb[MB][4];
