@@ -150,7 +150,7 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
   c.kv_tile = 64;
   c.tile_target = env_int("DELTAKV_TILE_TARGET", 3 * 256 / desc->n_kv_heads);
   // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
-  // item costs a ramp-up, a partial write and merge work, and longest-first dispatch balances the rest
+  // item costs a ramp-up, a partial write and merge work, and the planner's chains balance the rest
   c.stream_target = env_int("DELTAKV_STREAM_TARGET", 256 / desc->n_kv_heads);
   c.tile_wave_slots = env_int("DELTAKV_TILE_WAVE_SLOTS", std::max(1, 256 / desc->n_kv_heads));
   c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 128);
