@@ -374,3 +374,55 @@ def test_many_small_slots_walk_chains_of_units(n_slots, n_hi):
     check_close(out, ref, SMALL.dtype, f"{n_slots} slots")
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
     m.pool.close()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_batches_match_the_oracle(seed):
+    """Seeded random batch structures: slot count, histories (some grown over several appends and trimmed back,
+    some behind an aliased prefix), per-slot Delta from decode to several row tiles, idle slots, granule size,
+    staged or appended mode, two consecutive turns.  Whatever the planner makes of them -- row tiles, key chunks,
+    merge records, chains of streaming units -- every output row must match the oracle."""
+    rng = np.random.default_rng(9000 + seed)
+    sh = SMALL if seed % 3 else wl.Shape(16, 4, 128, "bf16")
+    n_slots = int(rng.integers(1, 13))
+    granule = int(rng.choice([16, 64, 256]))
+    hist = [int(rng.choice([0, rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 9000)])) for _ in range(n_slots)]
+    prefix = int(rng.integers(1, 700)) if n_slots > 1 and rng.random() < 0.6 else 0
+    m = Mirror(sh, n_slots, sum(hist) + prefix + n_slots * (2 * granule + 2100) + 4096, granule=granule, seed=seed)
+    slots = [m.acquire() for _ in range(n_slots)]
+    if prefix:
+        m.append([slots[0]], [prefix])
+        for s in slots[1:]:
+            if rng.random() < 0.7:
+                m.alias(slots[0], s, int(rng.integers(1, prefix + 1)))
+    for s, h in zip(slots, hist):
+        for part in np.diff(np.concatenate([[0], np.sort(rng.integers(0, h + 1, size=2)), [h]])).tolist():
+            if part:
+                m.append([s], [int(part)])
+        if h > 10 and rng.random() < 0.3:
+            m.trim(s, m.pool.length(s) - int(rng.integers(1, 10)))
+    choices = [0, 1, 1, 2, 5, 9, 16, 17, 40, 64, 65, 130, 300, 700, 1030]
+    for turn in range(2):
+        order = rng.permutation(n_slots).tolist()
+        sl = [slots[i] for i in order]
+        dl = [int(rng.choice(choices)) for _ in sl]
+        if sum(dl) == 0:
+            dl[0] = 3
+        total = sum(dl)
+        q = m.draw(total, sh.n_q_heads)
+        kn, vn = m.draw(total, sh.n_kv_heads), m.draw(total, sh.n_kv_heads)
+        cu = np.concatenate([[0], np.cumsum(dl)]).astype(np.int32)
+        if rng.random() < 0.5:  # staged: attend first, then append what was accepted
+            out = m.pool.attend(sl, cu, to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
+            ref, _ = oracle.delta_attend_batch(q, [m.cache(s) for s in sl], kn, vn, cu, sh.scale)
+            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} staged", scale_abs=True)
+            m.append(sl, dl, kn, vn, n_accept=[int(rng.integers(0, d + 1)) for d in dl])
+        else:
+            m.append(sl, dl, kn, vn)
+            out, lse, _ = m.attend_appended(sl, dl, q, lse=True)
+            ref, ref_lse = m.oracle_appended(sl, dl, q)
+            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} appended", scale_abs=True)
+            assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    for s in slots[:3]:
+        m.check_gather(s)
+    m.pool.close()
