@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   if (offsets_stale()) refresh_offsets();
   aim(2, 2);
   issue_all();
-  plain_s(k_ring, qf, sa, koff);
+  if (wave_active) plain_s(k_ring, qf, sa, koff);
   cnt0 = cnt1; pos0 = pos1;
   cnt1 = cnt2; pos1 = pos2;
   cnt2 = cnt3; pos2 = pos3;
@@ -502,6 +502,17 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   const long long wstart = wall_clock64();
 #endif
 
+  // on to step t+1
+  auto advance = [&]() __attribute__((always_inline)) {
+    cnt0 = cnt1; pos0 = pos1;
+    cnt1 = cnt2; pos1 = pos2;
+    cnt2 = cnt3; pos2 = pos3;
+    fetch();
+    k_rd = k_rd == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_rd + TILE_STAGE_BYTES;
+    k_wr = k_wr == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_wr + TILE_STAGE_BYTES;
+    v_rd = v_rd == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_rd + TILE_STAGE_BYTES;
+    v_wr = v_wr == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_wr + TILE_STAGE_BYTES;
+  };
   auto step = [&](f32x16(&sc)[2][MB], f32x16(&sn)[2][MB], u32x4(&pp)[MB][4], u32x4(&pc)[MB][4])
                   __attribute__((always_inline)) {
     wait_vmcnt<8>();
@@ -513,6 +524,14 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
     ld.gv = tl.v;
     ld.lds_k = k_ring_lds + k_wr;
     ld.lds_v = v_ring_lds + v_wr;
+    if (!wave_active) {
+      // A wavefront whose rows lie past the end of a ragged row tile only does its share of the loads and
+      // keeps the barriers: no arithmetic, so it draws no matrix-pipe power either.
+      if (offsets_stale()) refresh_offsets();
+      issue_all();
+      advance();
+      return;
+    }
     // a tile that does not exist or lies beyond the wavefront's rows counts as having no valid key
     const int cnt_eff = pos0 <= wave_max_limit ? cnt0 : 0;
     const bool need_mask = cnt_eff < TILE_KT || pos0 + TILE_KT - 1 > wave_min_limit;
@@ -568,15 +587,7 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
     DK_PROF_T(t3);
     DK_PROF_ADD(2, t3 - t1);
     DK_PROF_ADD(3, 1);
-    // on to step t+1
-    cnt0 = cnt1; pos0 = pos1;
-    cnt1 = cnt2; pos1 = pos2;
-    cnt2 = cnt3; pos2 = pos3;
-    fetch();
-    k_rd = k_rd == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_rd + TILE_STAGE_BYTES;
-    k_wr = k_wr == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_wr + TILE_STAGE_BYTES;
-    v_rd = v_rd == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_rd + TILE_STAGE_BYTES;
-    v_wr = v_wr == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_wr + TILE_STAGE_BYTES;
+    advance();
   };
 
   // steps 0 .. T for T tiles: the last one only applies P(T-1)
