@@ -352,8 +352,10 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   } else {
     e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (int32_t)plan.tile_items.size(), st);
     if (e != hipSuccess) return pool->hip_fail(e);
+    int32_t stream_rows = 0;
+    for (const DkItem& it : plan.stream_items) stream_rows = std::max(stream_rows, it.nrows);
     e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (const int32_t*)(ws + plan.off_links),
-                                 plan.stream_chains, st);
+                                 plan.stream_chains, stream_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
   if (timing) {

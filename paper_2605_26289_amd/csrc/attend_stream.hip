@@ -153,9 +153,11 @@ constexpr int STREAM_WAVE_BYTES = 2 * STREAM_STAGE_BYTES;      // 32 KiB
 constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages / the merge buffer
 constexpr int STREAM_LDS_BYTES = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
 
+// MB = 32-row blocks per unit: 1 when no unit of the launch has more than 32 packed rows (Delta <= 32 / G:
+// decode and short verify steps then skip the second, all-padding block), else 2.
+template <int MB>
 __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c, const int32_t* links, int n_chains) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  constexpr int MB = 2;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // The workgroup walks its chain of units (item, KV head); the planner balanced the chains against
@@ -285,19 +287,25 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c, const int3
 }  // namespace mfma
 
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
-                                hipStream_t stream) {
+                                int32_t max_rows, hipStream_t stream) {
   using namespace mfma;
   if (n_chains <= 0) return hipSuccess;
-  if (a.arena.head_dim != D || a.arena.dtype != 1) return hipErrorInvalidValue;
+  if (a.arena.head_dim != D || a.arena.dtype != 1 || max_rows > 64) return hipErrorInvalidValue;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_stream_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)attend_stream_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        STREAM_LDS_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)attend_stream_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              STREAM_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const Ctx c = make_ctx(a, items);
-  attend_stream_kernel<<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
+  if (max_rows <= 32)
+    attend_stream_kernel<1><<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
+  else
+    attend_stream_kernel<2><<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
   return hipGetLastError();
 }
 

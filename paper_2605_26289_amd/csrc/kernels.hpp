@@ -49,8 +49,9 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream);
 hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
 // Unit u = item u / n_kv_heads for KV head u % n_kv_heads.  Workgroup w walks the chain links[w],
 // links[n_chains + that unit], ... until a link is negative.
+// max_rows: the largest DkItem::nrows among the items (at most 64).
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
-                                hipStream_t stream);
+                                int32_t max_rows, hipStream_t stream);
 // max_rows: the largest DkMerge::nrows among them (sizes the grid).
 hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, int32_t max_rows,
                                hipStream_t stream);
