@@ -27,3 +27,28 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+# ---- parity report: worst errors of every oracle comparison, per test, at the end of a GPU run -------------
+_PARITY = []
+
+
+@pytest.fixture(autouse=True)
+def _collect_parity(request):
+    mod = sys.modules.get("gpu_util")
+    if mod is not None:
+        mod.WORST.clear()
+    yield
+    mod = sys.modules.get("gpu_util")
+    if mod is not None and mod.WORST:
+        _PARITY.append((request.node.nodeid, max(w[1] for w in mod.WORST), max(w[2] for w in mod.WORST),
+                        len(mod.WORST)))
+        mod.WORST.clear()
+
+
+def pytest_terminal_summary(terminalreporter):
+    if not _PARITY:
+        return
+    terminalreporter.section("oracle parity: worst max-abs / max-rel error per test")
+    for nodeid, a, r, n in _PARITY:
+        terminalreporter.write_line(f"{a:9.3e} {r:9.3e}  ({n:2d} comparisons)  {nodeid}")

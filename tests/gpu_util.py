@@ -28,20 +28,33 @@ def errors(gpu: np.ndarray, ref: np.ndarray):
     return float(diff.max()) if diff.size else 0.0, float(rel.max()) if rel.size else 0.0
 
 
-def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", rows=None, scale_abs=False):
-    """scale_abs: for synthetic edge cases with only a handful of keys the outputs reach |o| ~ 3, where
-    storing O in bf16 (half-ulp 2^-8 |o|) alone exceeds 1e-2; the absolute bound is then taken relative to
-    max(1, max|o|).  The five workload configs are always checked with scale_abs=False."""
+WORST = []  # (what, max abs, max rel) of every comparison made by check_close, for the test report
+
+
+def check_close(gpu: torch.Tensor, ref: np.ndarray, dtype: str, what: str = "", rows=None, row_scaled=False):
+    """Compares GPU output rows with the oracle's.
+
+    bf16: max |g - o| <= 1e-2 and max |g - o| / max(|o|, rms of the oracle row) <= 2e-2.
+    row_scaled (synthetic edge cases only, where a row sees a handful of keys and |o| reaches 3..4): the absolute
+    bound of a row becomes 1e-2 * max(1, max|o_row|) -- rows whose outputs stay below 1 keep the strict 1e-2.
+    Storing O in bf16 alone costs up to 2^-8 |o| (0.0078 in [2, 4)) and rounding the weights to bf16 another
+    2^-9 * sum_j p_j |v_j|, together more than 1e-2 at |o| ~ 3.  The five workload configs and the full-size
+    tests are always checked with the unscaled bounds."""
     g = gpu.float().cpu().numpy()
     if rows is not None:
         g, ref = g[rows], ref[rows]
     a, r = errors(g, ref)
+    WORST.append((what, a, r))
+    print(f"[parity] {what or 'rows'}: max abs {a:.3e}, max rel {r:.3e}, max|o| {float(np.abs(ref).max()) if ref.size else 0:.2f}")
     assert np.isfinite(g).all(), what
     if dtype == "f32":
         assert a <= F32_ABS_TOL, (what, a, r)
-    else:
-        bound = ABS_TOL * (max(1.0, float(np.abs(ref).max())) if scale_abs and ref.size else 1.0)
-        assert a <= bound and r <= REL_TOL, (what, a, r)
+    elif ref.size:
+        diff = np.abs(g.astype(np.float64) - ref)
+        bound = np.full(ref.shape[:-1] + (1,), ABS_TOL)
+        if row_scaled:
+            bound = ABS_TOL * np.maximum(1.0, np.abs(ref).max(axis=-1, keepdims=True))
+        assert (diff <= bound).all() and r <= REL_TOL, (what, a, r, float((diff / bound).max()))
     return a, r
 
 

@@ -120,11 +120,11 @@ def test_edge_shapes_appended_and_staged_agree_with_oracle(n, delta, variant):
     # staged on slot s
     out_s = m.pool.attend([s], [0, delta], to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
     ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
-    check_close(out_s, ref, sh.dtype, "staged", scale_abs=True)
+    check_close(out_s, ref, sh.dtype, "staged", row_scaled=True)
     # appended on slot t
     m.append([t], [delta], kn, vn)
     out_a, _, _ = m.attend_appended([t], [delta], q)
-    check_close(out_a, ref, sh.dtype, "appended", scale_abs=True)
+    check_close(out_a, ref, sh.dtype, "appended", row_scaled=True)
     m.pool.close()
 
 
@@ -146,7 +146,7 @@ def test_varlen_batch_with_empty_entries_and_mixed_delta(variant):
     m.append(sl, dl)
     out, lse, cu = m.attend_appended(sl, dl, q, lse=True)
     ref, ref_lse = m.oracle_appended(sl, dl, q)
-    check_close(out, ref, sh.dtype, "varlen", scale_abs=True)
+    check_close(out, ref, sh.dtype, "varlen", row_scaled=True)
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
     m.pool.close()
 
@@ -184,7 +184,12 @@ def test_aliased_prefix_reads_equal_private_copy():
     ref, _ = m.oracle_appended([b, c], [delta, delta], np.concatenate([q, q]))
     check_close(out, ref, sh.dtype, "alias vs private")
     assert np.array_equal(ref[:delta], ref[delta:])
-    assert (out[:delta].float() - out[delta:].float()).abs().max().item() <= 2e-3
+    # The two evaluations round their weights against different reference maxima and sum in a different order, so
+    # before the bf16 store they differ by a few 2^-9-relative terms; after it they are the same bf16 value or
+    # neighbouring ones.  With 650+ keys every |o| here is below 0.5, where neighbouring bf16 values are at most
+    # 2^-9 = 1.95e-3 apart: the bound is "one bf16 step at the outputs' magnitude".
+    assert np.abs(ref).max() < 0.5
+    assert (out[:delta].float() - out[delta:].float()).abs().max().item() <= 2.0 ** -9
     m.pool.close()
 
 
@@ -255,7 +260,7 @@ def test_growing_scores_exercise_the_lazy_rescale(delta):
     m.append([s], [n + delta], k, v)
     out, lse, _ = m.attend_appended([s], [delta], q, lse=True)
     ref, ref_lse = m.oracle_appended([s], [delta], q)
-    check_close(out, ref, sh.dtype, "growing scores", scale_abs=True)
+    check_close(out, ref, sh.dtype, "growing scores", row_scaled=True)
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < 5e-3 * max(1.0, np.abs(ref_lse).max() / 10)
     m.pool.close()
 
@@ -288,7 +293,7 @@ def test_group_sizes_from_mha_to_sixteen_heads_per_kv_head(hq, hkv, n, delta):
     q = m.draw(delta, hq)
     out = m.pool.attend([s], [0, delta], to_dev(q, "bf16"), sh.scale, to_dev(kn, "bf16"), to_dev(vn, "bf16"))
     ref, _ = oracle.delta_attend(q, *m.cache(s), kn, vn, sh.scale)
-    check_close(out, ref, "bf16", f"G={hq // hkv}", scale_abs=True)
+    check_close(out, ref, "bf16", f"G={hq // hkv}", row_scaled=True)
     m.pool.close()
 
 
@@ -310,10 +315,10 @@ def test_cells_outside_the_slot_never_reach_the_result(n, delta):
     assert torch.isfinite(out.float()).all()
     ref_a, _ = oracle.delta_attend(q[:delta], *m.cache(a), kn[:delta], vn[:delta], sh.scale)
     ref_b, _ = oracle.delta_attend(q[delta:], *m.cache(b), kn[delta:], vn[delta:], sh.scale)
-    check_close(out, np.concatenate([ref_a, ref_b]), sh.dtype, "canary", scale_abs=True)
+    check_close(out, np.concatenate([ref_a, ref_b]), sh.dtype, "canary", row_scaled=True)
     m.append([a, b], [delta, delta], kn, vn)   # appended mode reads the same cells back
     out2, _, _ = m.attend_appended([a, b], [delta, delta], q)
-    check_close(out2, np.concatenate([ref_a, ref_b]), sh.dtype, "canary appended", scale_abs=True)
+    check_close(out2, np.concatenate([ref_a, ref_b]), sh.dtype, "canary appended", row_scaled=True)
     m.pool.close()
 
 
@@ -415,13 +420,13 @@ def test_random_batches_match_the_oracle(seed):
         if rng.random() < 0.5:  # staged: attend first, then append what was accepted
             out = m.pool.attend(sl, cu, to_dev(q, sh.dtype), sh.scale, to_dev(kn, sh.dtype), to_dev(vn, sh.dtype))
             ref, _ = oracle.delta_attend_batch(q, [m.cache(s) for s in sl], kn, vn, cu, sh.scale)
-            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} staged", scale_abs=True)
+            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} staged", row_scaled=True)
             m.append(sl, dl, kn, vn, n_accept=[int(rng.integers(0, d + 1)) for d in dl])
         else:
             m.append(sl, dl, kn, vn)
             out, lse, _ = m.attend_appended(sl, dl, q, lse=True)
             ref, ref_lse = m.oracle_appended(sl, dl, q)
-            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} appended", scale_abs=True)
+            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} appended", row_scaled=True)
             assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
     for s in slots[:3]:
         m.check_gather(s)
