@@ -9,9 +9,10 @@ Parity status: every function here is pinned by the CPU test-suite (closed
 forms, brute force, a second independently written full recompute, a library
 attention routine, the paper's printed arithmetic; the verify step by a
 brute-force loop, hand cases and the equivalence with token-by-token
-decoding that the paper calls correctness-preserving; the radix cache by
-brute-force longest common prefixes, budget invariants and the paper's cached-token
-counts; the prompt-lookup search by a second formulation).  Parity unpinned: the
+decoding that the paper calls correctness-preserving; the prefix cache -- stated twice, as a
+flat ledger of saves (prefix_cache.py) and as a trie (radix.py) -- by brute-force longest common
+prefixes, a slow recount of the distinct positions held, budget invariants, a hand-checked shed
+order and the paper's cached-token counts; the prompt-lookup search by a second formulation).  Parity unpinned: the
 absolute output values of the five benchmark workloads are printed nowhere in the
 paper, so those are pinned only through these invariants.
 """
@@ -26,6 +27,7 @@ from .pool import OraclePool, OracleError  # noqa: F401
 from .verify import greedy_argmax, verify_accept, verify_batch, sequential_greedy  # noqa: F401
 from .pld import lookup_ngram, gate as pld_gate  # noqa: F401
 from .radix import OracleRadix  # noqa: F401
+from .prefix_cache import FlatPrefixCache  # noqa: F401
 from .sched import prefill_chunk, fnv1a32, prefill_groups  # noqa: F401
 from .costmodel import (  # noqa: F401
     prompt_lengths,

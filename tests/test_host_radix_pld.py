@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import OraclePool, OracleRadix
+from oracle import FlatPrefixCache, OraclePool, OracleRadix
 from paper_2605_26289_amd import binding as dk
 
 
@@ -22,14 +22,18 @@ def _rows(tokens):
 
 
 class Both:
-    """The library's trie on the library's pool next to the oracle trie on the oracle pool."""
+    """The library's trie on the library's pool, next to the flat ledger-of-saves model of the prefix cache (no trie:
+    cached length, leaves, shed order and cells held are all defined by comparing token strings) on an oracle pool.
+    The trie-shaped oracle runs alongside as a third statement of the same procedure."""
 
     def __init__(self, n_slots, n_session, budget):
         self.pool = _pool(n_slots, n_session)
         self.radix = dk.radix_create(self.pool, budget, 1)
         self.arena = np.zeros(1 << 16, dtype=np.int64)  # plays the K arena: one number per cell
         self.opool = OraclePool(n_slots, n_session)
-        self.oradix = OracleRadix(self.opool, budget)
+        self.flat = FlatPrefixCache(self.opool, budget)
+        self.tpool = OraclePool(n_slots, n_session)
+        self.trie = OracleRadix(self.tpool, budget)
 
     def close(self):
         dk.radix_destroy(self.radix)
@@ -38,23 +42,28 @@ class Both:
 
     def turn(self, tokens):
         slot = dk.seq_acquire(self.pool, 0)
-        oslot = self.opool.acquire(0)
+        oslot, tslot = self.opool.acquire(0), self.tpool.acquire(0)
         n_past = dk.radix_begin_turn(self.radix, slot, tokens)
-        assert n_past == self.oradix.begin_turn(oslot, tokens)
+        assert n_past == self.flat.begin_turn(oslot, tokens) == self.trie.begin_turn(tslot, tokens)
         assert dk.seq_len(self.pool, slot) == n_past
         rows = _rows(tokens)
         delta = len(tokens) - n_past
         cells = dk.kv_reserve(self.pool, [slot], [0, delta])      # only the delta is written
         self.arena[cells] = rows[n_past:]
-        self.opool.append(oslot, rows[n_past:].reshape(-1, 1, 1), rows[n_past:].reshape(-1, 1, 1))
+        for pool, sl in ((self.opool, oslot), (self.tpool, tslot)):
+            pool.append(sl, rows[n_past:].reshape(-1, 1, 1), rows[n_past:].reshape(-1, 1, 1))
         got = self.arena[dk.seq_cells(self.pool, slot)]
         assert np.array_equal(got, rows)                          # aliased prefix + delta read as the whole prompt
-        assert dk.radix_save(self.radix, slot, tokens) == self.oradix.save(oslot, tokens)
+        assert np.array_equal(self.opool.gather(oslot)[0].ravel(), rows)
+        assert dk.radix_save(self.radix, slot, tokens) == self.flat.save(oslot, tokens) == self.trie.save(tslot, tokens)
         dk.seq_release(self.pool, slot)
         self.opool.release(oslot)
+        self.tpool.release(tslot)
         nodes, cells_held, donors, shed = dk.radix_stats(self.radix)
-        assert (nodes, cells_held, donors, shed) == (self.oradix.node_count(), self.oradix.cells,
-                                                     len(self.oradix.donor_refs), len(self.oradix.evicted))
+        assert (nodes, cells_held, donors, shed) == (self.flat.piece_count(), self.flat.cells, self.flat.donors(),
+                                                     len(self.flat.evicted))
+        assert cells_held == self.flat.distinct_positions() == self.opool.live_cells()
+        assert (nodes, cells_held, shed) == (self.trie.node_count(), self.trie.cells, len(self.trie.evicted))
         held, _free = dk.pool_stats(self.pool)
         assert held >= cells_held  # cells are handed out in granules, so the pool may hold a little more
         return n_past
@@ -80,7 +89,7 @@ def test_random_traffic_with_eviction_matches_the_oracle_step_by_step(seed):
     shed = dk.radix_stats(b.radix)[3]
     assert shed > 10
     for i in range(shed):
-        assert tuple(dk.radix_evicted_path(b.radix, i)) == b.oradix.evicted[i]
+        assert tuple(dk.radix_evicted_path(b.radix, i)) == b.flat.evicted[i] == b.trie.evicted[i]
     b.close()
 
 

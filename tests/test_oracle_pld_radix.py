@@ -3,7 +3,14 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import OraclePool, OracleRadix
+from oracle import FlatPrefixCache, OraclePool, OracleRadix
+
+# the prefix cache is stated twice (flat ledger of saves, trie); every pin below holds for both
+CACHES = [FlatPrefixCache, OracleRadix]
+
+
+def _pieces(c):
+    return c.piece_count() if isinstance(c, FlatPrefixCache) else c.node_count()
 
 
 # ---- prompt lookup ---------------------------------------------------------------------------------
@@ -110,7 +117,8 @@ def _turn(pool, radix, tokens):
     return n_past
 
 
-def test_five_turn_conversation_returns_the_papers_cached_counts():
+@pytest.mark.parametrize("Cache", CACHES)
+def test_five_turn_conversation_returns_the_papers_cached_counts(Cache):
     """Sec. 1 / Sec. 4.1: a 200-token system prompt, +150 tokens per turn, 950 tokens on turn 5, 800 of them cached."""
     gold = {}
     for line in open(__file__.replace("test_oracle_pld_radix.py", "golden/paper_arithmetic.txt")):
@@ -120,18 +128,19 @@ def test_five_turn_conversation_returns_the_papers_cached_counts():
     rng = np.random.default_rng(0)
     stream = rng.integers(0, 50000, size=950).tolist()
     pool = OraclePool(8, 6)
-    radix = OracleRadix(pool, cell_budget=4096)
+    radix = Cache(pool, cell_budget=4096)
     got = [_turn(pool, radix, stream[: 200 + 150 * t]) for t in range(6)]
     assert got == [0, 200, 350, 500, 650, 800]
     assert got[-1] == int(gold["final_turn_cached_tokens"]) and 200 + 150 * 5 == int(gold["final_prompt_tokens"])
-    assert radix.node_count() == 6 and radix.cells == 950 == pool.live_cells()  # one node per turn, delta cells only
+    assert _pieces(radix) == 6 and radix.cells == 950 == pool.live_cells()  # one node per turn, delta cells only
 
 
+@pytest.mark.parametrize("Cache", CACHES)
 @pytest.mark.parametrize("seed", range(5))
-def test_n_past_is_the_longest_common_prefix_with_anything_saved(seed):
+def test_n_past_is_the_longest_common_prefix_with_anything_saved(seed, Cache):
     rng = np.random.default_rng(seed)
     pool = OraclePool(40, 36)
-    radix = OracleRadix(pool, cell_budget=10 ** 6)
+    radix = Cache(pool, cell_budget=10 ** 6)
     saved = []
     for _ in range(30):
         if saved and rng.random() < 0.7:   # extend or fork an earlier prompt
@@ -152,11 +161,12 @@ def test_n_past_is_the_longest_common_prefix_with_anything_saved(seed):
         assert radix.cells == pool.live_cells()  # the trie holds exactly the distinct cells, no copies
 
 
-def test_leaf_oldest_eviction_keeps_the_shared_branch_and_sheds_stale_tails():
+@pytest.mark.parametrize("Cache", CACHES)
+def test_leaf_oldest_eviction_keeps_the_shared_branch_and_sheds_stale_tails(Cache):
     system = list(range(1000, 1100))                 # shared preamble, 100 tokens
     tails = [[10 + i] * 40 for i in range(4)]        # four conversations, 40 private tokens each
     pool = OraclePool(12, 8)
-    radix = OracleRadix(pool, cell_budget=100 + 3 * 40)
+    radix = Cache(pool, cell_budget=100 + 3 * 40)
     assert _turn(pool, radix, system) == 0
     for i in range(3):
         assert _turn(pool, radix, system + tails[i]) == 100
@@ -171,15 +181,49 @@ def test_leaf_oldest_eviction_keeps_the_shared_branch_and_sheds_stale_tails():
     assert radix.cells <= radix.budget
 
 
-def test_budget_and_donor_slots_never_exceeded_under_random_traffic():
+@pytest.mark.parametrize("Cache", CACHES)
+def test_budget_and_donor_slots_never_exceeded_under_random_traffic(Cache):
     rng = np.random.default_rng(3)
     pool = OraclePool(10, 6)
-    radix = OracleRadix(pool, cell_budget=150)
+    radix = Cache(pool, cell_budget=150)
     prompts = [rng.integers(0, 4, size=30).tolist() for _ in range(4)]
     for step in range(200):
         base = prompts[int(rng.integers(len(prompts)))]
         t = base[: int(rng.integers(1, 31))] + rng.integers(0, 4, size=int(rng.integers(0, 25))).tolist()
         _turn(pool, radix, t)
         assert radix.cells <= 150 and radix.cells == pool.live_cells()
-        assert sum(pool.in_use[4:]) == len(radix.donor_refs) <= 6
+        assert sum(pool.in_use[4:]) == (radix.donors() if Cache is FlatPrefixCache else len(radix.donor_refs)) <= 6
     assert len(radix.evicted) > 10
+
+
+# ---- the flat ledger on its own terms -------------------------------------------------------------
+
+def test_flat_ledger_counts_every_held_position_once():
+    """cells (sum of the saves' ranges) == a slow recount of the distinct prompt prefixes covered == the distinct
+    cell objects alive in the pool, under traffic that forks, extends, cuts pieces and sheds leaves."""
+    rng = np.random.default_rng(5)
+    pool = OraclePool(12, 8)
+    cache = FlatPrefixCache(pool, cell_budget=120)
+    prompts = [rng.integers(0, 3, size=25).tolist() for _ in range(3)]
+    for _ in range(120):
+        base = prompts[int(rng.integers(len(prompts)))]
+        t = base[: int(rng.integers(1, 26))] + rng.integers(0, 3, size=int(rng.integers(0, 20))).tolist()
+        _turn(pool, cache, t)
+        assert cache.cells == cache.distinct_positions() == pool.live_cells() <= 120
+    assert len(cache.evicted) > 5
+
+
+def test_flat_ledger_hand_case_cut_piece_ages_separately():
+    """Save abcdef, then abcxy: the first save's piece is cut at 3; shedding takes def or xy (leaves), never abc
+    while something hangs below it; what is cached of 'abcdz' drops from 5 to 3 once def is shed."""
+    a, b, c, d, e, f, x, y, z = range(1, 10)
+    pool = OraclePool(8, 6)
+    cache = FlatPrefixCache(pool, cell_budget=8)
+    _turn(pool, cache, [a, b, c, d, e, f])                 # 6 cells
+    assert _turn(pool, cache, [a, b, c, x, y]) == 3       # + 2 cells, cuts the first piece at 3
+    assert cache.piece_count() == 3 and cache.cells == 8
+    assert cache.cached([a, b, c, d, z]) == 4
+    assert _turn(pool, cache, [a, b, c, x, y, z]) == 5    # needs 1 cell: the stalest leaf is def
+    assert cache.evicted == [(a, b, c, d, e, f)]
+    assert cache.cached([a, b, c, d, z]) == 3 and cache.cells == 6
+    assert pool.live_cells() == 6
