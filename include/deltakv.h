@@ -2,8 +2,8 @@
  * deltakv -- delta-prefill attention over a pooled, prefix-aliased KV cache (MI355X / gfx950).
  *
  * C ABI of the library.  Plain C types only.  Every pointer argument is marked
- * HOST or DEVICE.  Device buffers are allocated and owned by the caller; the
- * library owns host metadata and a small ring of pinned host staging buffers.
+ * HOST or DEVICE.  Device buffers and the pinned host staging memory are allocated
+ * and owned by the caller; the library owns host metadata only.
  *
  * General rules
  *   - every function returns an int32_t status (DK_OK == 0, errors negative), never
@@ -11,10 +11,13 @@
  *   - a call that fails leaves the pool's state unchanged;
  *   - calls that launch GPU work (dk_kv_append, dk_delta_attend, dk_seq_gather) are
  *     asynchronous on the HIP stream passed as `stream` (a hipStream_t cast to void*,
- *     NULL = the default stream) and never synchronise the device.  They read the
- *     slot metadata at call time, so later host-side calls (trim, release, alias) do
- *     not affect work already enqueued.  All GPU-launching calls on one pool must be
- *     issued on one stream, or be ordered by the caller;
+ *     NULL = the default stream).  They never wait for the device and never allocate
+ *     device or pinned memory: descriptors travel through the caller's staging memory
+ *     (dk_pool_desc::host_staging), and a call that finds every staging buffer still
+ *     in flight returns DK_ERR_BUSY instead of waiting.  They read the slot metadata
+ *     at call time, so later host-side calls (trim, release, alias) do not affect
+ *     work already enqueued.  All GPU-launching calls on one pool must be issued on
+ *     one stream, or be ordered by the caller;
  *   - host-only calls are thread-safe (one mutex per pool, paper Sec. 3.1).
  *
  * Vocabulary (paper Sec. 2.2, 3.1, 3.3): a *slot* is one named sequence sigma_i of the
@@ -43,7 +46,10 @@ enum {
   DK_ERR_DUP_SLOT = -5,    /* the same slot listed twice in one batched call */
   DK_ERR_UNSUPPORTED = -6, /* shape / dtype / alias form the library does not implement */
   DK_ERR_WORKSPACE = -7,   /* workspace missing or too small */
-  DK_ERR_HIP = -8          /* a HIP runtime call failed (see dk_last_hip_error) */
+  DK_ERR_HIP = -8,         /* a HIP runtime call failed (see dk_last_hip_error) */
+  DK_ERR_BUSY = -9,        /* every staging buffer still carries an unfinished upload: nothing was enqueued;
+                              synchronise the stream (or wait for earlier work) and call again */
+  DK_ERR_NO_MEMORY = -10   /* the host ran out of memory for metadata */
 };
 
 /*
@@ -59,6 +65,12 @@ enum {
  * session region.
  * dev_meta: DEVICE scratch of at least dk_meta_bytes() bytes, caller-owned, used for
  * the per-call copy tables of dk_kv_append / dk_seq_gather.
+ * host_staging: HOST memory, pinned (hipHostMalloc), 256-byte aligned, caller-owned, must outlive
+ * the pool.  It is cut into staging_depth (0 selects 8, at most 64) equal buffers of at least
+ * 64 KiB through which the descriptors of a launching call are uploaded; dk_staging_bytes() is the
+ * recommended size (1 MiB per buffer).  A call whose descriptors exceed one buffer, or any call
+ * that needs an upload on a pool created with host_staging == NULL, returns DK_ERR_WORKSPACE
+ * (appends of at most 896 tokens need no upload).  NULL is meant for host-only use of the pool.
  */
 typedef struct {
   int32_t n_slots;
@@ -73,14 +85,20 @@ typedef struct {
   void* v_arena; /* DEVICE */
   void* dev_meta; /* DEVICE */
   int64_t dev_meta_bytes;
+  void* host_staging; /* HOST, pinned; NULL: no staging */
+  int64_t host_staging_bytes;
+  int32_t staging_depth;
 } dk_pool_desc;
 
 /* Bytes of dev_meta a pool of this description needs.  HOST only. */
 int32_t dk_meta_bytes(const dk_pool_desc* desc, int64_t* bytes_out);
+/* Recommended bytes of host_staging for this description (staging_depth buffers of 1 MiB).  HOST only. */
+int32_t dk_staging_bytes(const dk_pool_desc* desc, int64_t* bytes_out);
 
 /*
  * pool_create (paper Sec. 3.1).  Builds the slot table, the two free lists and the cell
- * allocator.  Touches no device memory.  DK_ERR_INVALID on a malformed description,
+ * allocator.  Touches no device memory and allocates none; with host_staging it creates one HIP
+ * event per staging buffer (needs a current device).  DK_ERR_INVALID on a malformed description,
  * DK_ERR_UNSUPPORTED for head_dim not in {64, 128}, n_q_heads not a multiple of
  * n_kv_heads, or an unknown dtype.
  */
@@ -273,7 +291,21 @@ int32_t dk_pool_stats(dk_pool* pool, int64_t* cells_held_out, int64_t* cells_fre
 /* Kernel selection for dk_delta_attend: 0 automatic (default), 1 force the scalar reference kernel. */
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
 /*
- * Device time of the attention kernels (not the descriptor upload, not the merge kernel) of recent
+ * Planner tuning, per pool; the defaults suit an MI355X (256 compute units in 8 XCDs) and the library
+ * reads no environment variable.  Names and ranges (DK_ERR_UNSUPPORTED for an unknown name,
+ * DK_ERR_INVALID for a value out of range or not whole where a count is meant):
+ *   stream_target     aimed number of streaming work items per KV head             [1, 2^20]      default 256 / Hkv
+ *   stream_min_chunk  smallest key range worth its own streaming item               [64, 2^24]     default 512
+ *   stream_chains     workgroups of the streaming kernel (one per compute unit)     [1, 65536]     default 256
+ *   stream_item_cost  fixed cost of a streaming unit in the chain balance, in keys  [0, 2^20]      default 512
+ *   tile_wave_slots   tile-kernel workgroups of one KV head that run at a time      [1, 65536]     default 256 / Hkv
+ *   tile_min_chunk    smallest key range worth its own tile item                    [64, 2^24]     default 128
+ *   xcd_speed0 .. xcd_speed7  relative K/V streaming rate of each XCD               (0, 100]       default 1
+ * Affects only how later calls cut and order their work, never their results' meaning.
+ */
+int32_t dk_set_tuning(dk_pool* pool, const char* name, double value);
+/*
+ * Device time of the attention work (tile, streaming and merge kernels; not the descriptor upload) of recent
  * dk_delta_attend calls on this pool, measured with HIP events recorded on the call's stream.
  * dk_set_attend_timing(pool, n): keep the last n calls (0 <= n <= 256; 0 switches recording off).
  * dk_attend_times: waits for the recorded work, then writes the durations in milliseconds, oldest

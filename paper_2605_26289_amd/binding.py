@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libdeltakv.so")
 F32, BF16 = 0, 1
 OK = 0
 STATUS_NAMES = {0: "OK", -1: "INVALID", -2: "TIMEOUT", -3: "NO_CELLS", -4: "NO_SLOT", -5: "DUP_SLOT",
-                -6: "UNSUPPORTED", -7: "WORKSPACE", -8: "HIP"}
+                -6: "UNSUPPORTED", -7: "WORKSPACE", -8: "HIP", -9: "BUSY", -10: "NO_MEMORY"}
+BUSY = -9
 
 
 class DeltaKVError(RuntimeError):
@@ -32,7 +33,8 @@ class PoolDesc(C.Structure):
     _fields_ = [("n_slots", C.c_int32), ("n_session_slots", C.c_int32), ("arena_cells", C.c_int64),
                 ("granule_cells", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("dtype", C.c_int32), ("k_arena", C.c_void_p), ("v_arena", C.c_void_p),
-                ("dev_meta", C.c_void_p), ("dev_meta_bytes", C.c_int64)]
+                ("dev_meta", C.c_void_p), ("dev_meta_bytes", C.c_int64), ("host_staging", C.c_void_p),
+                ("host_staging_bytes", C.c_int64), ("staging_depth", C.c_int32)]
 
 
 _lib = None
@@ -42,6 +44,8 @@ _I64P = C.POINTER(C.c_int64)
 
 SIGNATURES = {
     "dk_meta_bytes": (C.c_int32, [C.POINTER(PoolDesc), _I64P]),
+    "dk_staging_bytes": (C.c_int32, [C.POINTER(PoolDesc), _I64P]),
+    "dk_set_tuning": (C.c_int32, [C.c_void_p, C.c_char_p, C.c_double]),
     "dk_pool_create": (C.c_int32, [C.POINTER(PoolDesc), C.POINTER(C.c_void_p)]),
     "dk_pool_destroy": (C.c_int32, [C.c_void_p]),
     "dk_seq_acquire": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64, _I32P]),
@@ -133,6 +137,27 @@ def meta_bytes(desc: PoolDesc) -> int:
     return out.value
 
 
+def staging_bytes(desc: PoolDesc) -> int:
+    out = C.c_int64()
+    _check(lib().dk_staging_bytes(C.byref(desc), C.byref(out)), "staging_bytes")
+    return out.value
+
+
+def set_tuning(pool, name: str, value: float) -> None:
+    _check(lib().dk_set_tuning(pool, name.encode(), float(value)), f"set_tuning({name})")
+
+
+def _launch(call, where: str, pool, stream):
+    """Runs a launching call; when every staging buffer is still in flight (BUSY) waits for the stream and repeats.
+    The C ABI itself never waits: back-pressure is the caller's policy, and this is the binding's."""
+    rc = call()
+    while rc == BUSY:
+        import torch
+        (torch.cuda.current_stream() if stream is None else stream).synchronize()
+        rc = call()
+    _check(rc, where, pool)
+
+
 def pool_create(desc: PoolDesc) -> C.c_void_p:
     out = C.c_void_p()
     _check(lib().dk_pool_create(C.byref(desc), C.byref(out)), "pool_create")
@@ -185,8 +210,9 @@ def kv_append(pool, slots, cu_delta, k_new, v_new, n_accept=None, stream=None) -
     s_arr, s_p = _i32(slots)
     c_arr, c_p = _i32(cu_delta)
     a_arr, a_p = _i32(n_accept)
-    _check(lib().dk_kv_append(pool, len(s_arr), s_p, c_p, a_p, _ptr(k_new), _ptr(v_new), _stream(stream)),
-           "kv_append", pool)
+    st = _stream(stream)
+    _launch(lambda: lib().dk_kv_append(pool, len(s_arr), s_p, c_p, a_p, _ptr(k_new), _ptr(v_new), st),
+            "kv_append", pool, stream)
 
 
 def kv_reserve(pool, slots, cu_delta, n_accept=None) -> np.ndarray:
@@ -212,9 +238,10 @@ def delta_attend(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=
     s_arr, s_p = _i32(slots)
     c_arr, c_p = _i32(cu_delta)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new), float(scale),
-                                 _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream)),
-           "delta_attend", pool)
+    st = _stream(stream)
+    _launch(lambda: lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                          float(scale), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, st),
+            "delta_attend", pool, stream)
 
 
 def verify_workspace_bytes(total_rows: int, vocab: int, dtype: int) -> int:
@@ -323,7 +350,8 @@ def prefill_groups(prompts, n_past, prefix_id, window: int = 8):
 
 
 def seq_gather(pool, slot: int, k_out, v_out, stream=None) -> None:
-    _check(lib().dk_seq_gather(pool, slot, _ptr(k_out), _ptr(v_out), _stream(stream)), "seq_gather", pool)
+    st = _stream(stream)
+    _launch(lambda: lib().dk_seq_gather(pool, slot, _ptr(k_out), _ptr(v_out), st), "seq_gather", pool, stream)
 
 
 def set_attend_variant(pool, variant: int) -> None:

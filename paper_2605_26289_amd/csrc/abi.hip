@@ -1,6 +1,6 @@
 // C ABI of libdeltakv (see include/deltakv.h): argument checking, host bookkeeping, descriptor
-// upload and kernel launches.  Nothing here synchronises the device except the reuse guard of the
-// pinned staging ring and dk_last_attend_ms.
+// upload and kernel launches.  Launching calls neither allocate device or pinned memory nor wait for
+// the device; only dk_pool_destroy and dk_attend_times wait (for the work they are asked about).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
 #include <vector>
 
 #include "../../include/deltakv.h"
@@ -19,18 +20,27 @@
 namespace {
 
 constexpr int64_t kMetaBytes = 1 << 20;  // device scratch for copy tables: 256k tokens per launch
-constexpr int kRing = 4;
+constexpr int kMaxRing = 64;
+constexpr int kDefaultRing = 8;
+constexpr int64_t kMinStageBytes = 64 << 10;
 
+// One buffer of the caller's pinned staging memory and the event that tells when its last upload is done.
 struct Staging {
-  void* host = nullptr;
-  size_t cap = 0;
+  char* host = nullptr;
   hipEvent_t done = nullptr;
   bool in_flight = false;
 };
 
-int32_t env_int(const char* name, int32_t dflt) {
-  const char* v = std::getenv(name);
-  return (v && *v) ? std::atoi(v) : dflt;
+// Exceptions must not cross the C boundary: host containers may throw std::bad_alloc.
+template <typename F>
+int32_t guarded(F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return DK_ERR_NO_MEMORY;
+  } catch (...) {
+    return DK_ERR_INVALID;
+  }
 }
 
 }  // namespace
@@ -39,13 +49,16 @@ struct dk_pool {
   dk_pool_desc desc;
   dk::Pool meta;
   dk::PlanConfig cfg;
-  Staging ring[kRing];
+  Staging ring[kMaxRing];
+  int ring_size = 0;
   int ring_next = 0;
+  size_t stage_cap = 0;  // bytes per staging buffer
   int32_t variant = 0;
   std::vector<hipEvent_t> ev0, ev1;  // ring of start/stop events around the attention kernels
   int64_t ev_calls = 0;              // calls recorded since timing was switched on
   int32_t last_hip = 0;
-  std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring and dev_meta)
+  std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring, dev_meta and plan)
+  dk::AttendPlan plan;   // reused from call to call so that steady-state planning allocates nothing
 
   dk_pool(const dk_pool_desc& d, int32_t granule)
       : desc(d), meta(d.n_slots, d.n_session_slots, d.arena_cells, granule) {}
@@ -60,29 +73,19 @@ struct dk_pool {
     return DK_ERR_HIP;
   }
 
-  // A pinned host buffer of at least `bytes`, safe to overwrite (its previous upload has finished).
+  // The next staging buffer, if the upload that last used it has finished.  Never waits and never
+  // allocates: DK_ERR_BUSY when every buffer is still in flight, DK_ERR_WORKSPACE when the pool was
+  // created without staging memory or `bytes` exceeds one buffer.
   int32_t stage(size_t bytes, Staging** out) {
+    if (ring_size == 0 || bytes > stage_cap) return DK_ERR_WORKSPACE;
     Staging& s = ring[ring_next];
-    ring_next = (ring_next + 1) % kRing;
-    if (!s.done) {
-      hipError_t e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
-      if (e != hipSuccess) return hip_fail(e);
-    }
     if (s.in_flight) {
-      hipError_t e = hipEventSynchronize(s.done);
+      const hipError_t e = hipEventQuery(s.done);
+      if (e == hipErrorNotReady) return DK_ERR_BUSY;
       if (e != hipSuccess) return hip_fail(e);
       s.in_flight = false;
     }
-    if (s.cap < bytes) {
-      if (s.host) (void)hipHostFree(s.host);
-      s.host = nullptr;
-      s.cap = 0;
-      size_t cap = 1 << 16;
-      while (cap < bytes) cap <<= 1;
-      hipError_t e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
-      if (e != hipSuccess) return hip_fail(e);
-      s.cap = cap;
-    }
+    ring_next = (ring_next + 1) % ring_size;
     *out = &s;
     return DK_OK;
   }
@@ -94,6 +97,16 @@ struct dk_pool {
     if (e != hipSuccess) return hip_fail(e);
     s->in_flight = true;
     return DK_OK;
+  }
+
+  void drop_events() {
+    for (int i = 0; i < ring_size; ++i)
+      if (ring[i].done) (void)hipEventDestroy(ring[i].done);
+    for (hipEvent_t e : ev0) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ev1) (void)hipEventDestroy(e);
+    ring_size = 0;
+    ev0.clear();
+    ev1.clear();
   }
 };
 
@@ -125,62 +138,103 @@ int32_t dk_meta_bytes(const dk_pool_desc* desc, int64_t* bytes_out) {
   return DK_OK;
 }
 
-int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
+int32_t dk_staging_bytes(const dk_pool_desc* desc, int64_t* bytes_out) {
   int32_t why;
-  if (!pool_out) return DK_ERR_INVALID;
-  *pool_out = nullptr;
+  if (!bytes_out) return DK_ERR_INVALID;
   if (!desc_ok(desc, &why)) return why;
-  if (!desc->k_arena || !desc->v_arena || !desc->dev_meta || desc->dev_meta_bytes < kMetaBytes) return DK_ERR_INVALID;
-  if (((uintptr_t)desc->k_arena | (uintptr_t)desc->v_arena | (uintptr_t)desc->dev_meta) & 255) return DK_ERR_INVALID;
-  const int32_t granule = desc->granule_cells ? desc->granule_cells : 256;
-  if (desc->arena_cells / granule <= 0) return DK_ERR_INVALID;
-  if (desc->arena_cells > INT32_MAX) return DK_ERR_UNSUPPORTED;
-  dk_pool* p = new (std::nothrow) dk_pool(*desc, granule);
-  if (!p) return DK_ERR_INVALID;
-  // The arena keeps the caller's stride: rows of KV head g start at g * arena_cells.
-  p->meta_arena_cells = desc->arena_cells;
-  const int32_t group = desc->n_q_heads / desc->n_kv_heads;
-  dk::PlanConfig& c = p->cfg;
-  c.n_q_heads = desc->n_q_heads;
-  c.n_kv_heads = desc->n_kv_heads;
-  c.head_dim = desc->head_dim;
-  c.use_mfma = desc->dtype == DK_BF16 && desc->head_dim == 128 && is_pow2(group) && group <= 16;
-  c.tile_rows = 256;
-  c.stream_rows = 64;
-  c.kv_tile = 64;
-  c.tile_target = env_int("DELTAKV_TILE_TARGET", 3 * 256 / desc->n_kv_heads);
-  // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
-  // item costs a ramp-up, a partial write and merge work, and the planner's chains balance the rest
-  c.stream_target = env_int("DELTAKV_STREAM_TARGET", 256 / desc->n_kv_heads);
-  c.tile_wave_slots = env_int("DELTAKV_TILE_WAVE_SLOTS", std::max(1, 256 / desc->n_kv_heads));
-  c.tile_min_chunk = env_int("DELTAKV_TILE_MIN_CHUNK", 128);
-  c.stream_min_chunk = env_int("DELTAKV_STREAM_MIN_CHUNK", 512);
-  c.stream_chains = env_int("DELTAKV_STREAM_CHAINS", 256);
-  c.stream_item_cost = env_int("DELTAKV_STREAM_ITEM_COST", 512);
-  for (float& x : c.xcd_speed) x = 1.f;
-  if (const char* v = std::getenv("DELTAKV_XCD_SPEEDS")) {  // eight comma-separated relative rates
-    float f[8];
-    if (std::sscanf(v, "%f,%f,%f,%f,%f,%f,%f,%f", &f[0], &f[1], &f[2], &f[3], &f[4], &f[5], &f[6], &f[7]) == 8)
-      for (int x = 0; x < 8; ++x)
-        if (f[x] > 0.f) c.xcd_speed[x] = f[x];
-  }
-  if (c.tile_target < 1) c.tile_target = 1;
-  if (c.stream_target < 1) c.stream_target = 1;
-  *pool_out = p;
+  const int64_t depth = desc->staging_depth ? desc->staging_depth : kDefaultRing;
+  if (depth < 1 || depth > kMaxRing) return DK_ERR_INVALID;
+  *bytes_out = depth * kMetaBytes;
   return DK_OK;
+}
+
+int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
+  return guarded([&]() -> int32_t {
+    int32_t why;
+    if (!pool_out) return DK_ERR_INVALID;
+    *pool_out = nullptr;
+    if (!desc_ok(desc, &why)) return why;
+    if (!desc->k_arena || !desc->v_arena || !desc->dev_meta || desc->dev_meta_bytes < kMetaBytes) return DK_ERR_INVALID;
+    if (((uintptr_t)desc->k_arena | (uintptr_t)desc->v_arena | (uintptr_t)desc->dev_meta) & 255) return DK_ERR_INVALID;
+    const int32_t granule = desc->granule_cells ? desc->granule_cells : 256;
+    if (desc->arena_cells / granule <= 0) return DK_ERR_INVALID;
+    if (desc->arena_cells > INT32_MAX) return DK_ERR_UNSUPPORTED;
+    const int32_t depth = desc->staging_depth ? desc->staging_depth : kDefaultRing;
+    if (depth < 1 || depth > kMaxRing || desc->host_staging_bytes < 0) return DK_ERR_INVALID;
+    if ((desc->host_staging == nullptr) != (desc->host_staging_bytes == 0)) return DK_ERR_INVALID;
+    if (desc->host_staging && (((uintptr_t)desc->host_staging & 255) || desc->host_staging_bytes / depth < kMinStageBytes))
+      return DK_ERR_INVALID;
+    dk_pool* p = new dk_pool(*desc, granule);
+    // The arena keeps the caller's stride: rows of KV head g start at g * arena_cells.
+    p->meta_arena_cells = desc->arena_cells;
+    if (desc->host_staging) {
+      p->stage_cap = (size_t)(desc->host_staging_bytes / depth) & ~(size_t)255;
+      for (int i = 0; i < depth; ++i) {
+        p->ring[i].host = (char*)desc->host_staging + (size_t)i * p->stage_cap;
+        const hipError_t e = hipEventCreateWithFlags(&p->ring[i].done, hipEventDisableTiming);
+        if (e != hipSuccess) {
+          p->drop_events();
+          delete p;
+          return DK_ERR_HIP;
+        }
+        p->ring_size = i + 1;
+      }
+    }
+    const int32_t group = desc->n_q_heads / desc->n_kv_heads;
+    dk::PlanConfig& c = p->cfg;
+    c.n_q_heads = desc->n_q_heads;
+    c.n_kv_heads = desc->n_kv_heads;
+    c.head_dim = desc->head_dim;
+    c.use_mfma = desc->dtype == DK_BF16 && desc->head_dim == 128 && is_pow2(group) && group <= 16;
+    c.tile_rows = 256;
+    c.stream_rows = 64;
+    c.kv_tile = 64;
+    c.tile_target = 3 * 256 / desc->n_kv_heads;
+    // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
+    // item costs a ramp-up, a partial write and merge work, and the planner's chains balance the rest
+    c.stream_target = std::max(1, 256 / desc->n_kv_heads);
+    c.tile_wave_slots = std::max(1, 256 / desc->n_kv_heads);
+    c.tile_min_chunk = 128;
+    c.stream_min_chunk = 512;
+    c.stream_chains = 256;
+    c.stream_item_cost = 512;
+    for (float& x : c.xcd_speed) x = 1.f;
+    *pool_out = p;
+    return DK_OK;
+  });
 }
 
 int32_t dk_pool_destroy(dk_pool* pool) {
   if (!pool) return DK_ERR_INVALID;
-  for (Staging& s : pool->ring) {
-    if (s.in_flight) (void)hipEventSynchronize(s.done);
-    if (s.host) (void)hipHostFree(s.host);
-    if (s.done) (void)hipEventDestroy(s.done);
-  }
-  for (hipEvent_t e : pool->ev0) (void)hipEventDestroy(e);
-  for (hipEvent_t e : pool->ev1) (void)hipEventDestroy(e);
+  for (int i = 0; i < pool->ring_size; ++i)
+    if (pool->ring[i].in_flight) (void)hipEventSynchronize(pool->ring[i].done);
+  pool->drop_events();
   delete pool;
   return DK_OK;
+}
+
+int32_t dk_set_tuning(dk_pool* pool, const char* name, double value) {
+  if (!pool || !name || !(value == value)) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  dk::PlanConfig& c = pool->cfg;
+  const std::string key(name);
+  const auto whole = [&](int32_t lo, int32_t hi, int32_t* dst) -> int32_t {
+    if (value < lo || value > hi || value != (double)(int64_t)value) return DK_ERR_INVALID;
+    *dst = (int32_t)value;
+    return DK_OK;
+  };
+  if (key == "stream_target") return whole(1, 1 << 20, &c.stream_target);
+  if (key == "stream_min_chunk") return whole(64, 1 << 24, &c.stream_min_chunk);
+  if (key == "stream_chains") return whole(1, 1 << 16, &c.stream_chains);
+  if (key == "stream_item_cost") return whole(0, 1 << 20, &c.stream_item_cost);
+  if (key == "tile_wave_slots") return whole(1, 1 << 16, &c.tile_wave_slots);
+  if (key == "tile_min_chunk") return whole(64, 1 << 24, &c.tile_min_chunk);
+  if (key.size() == 10 && key.compare(0, 9, "xcd_speed") == 0 && key[9] >= '0' && key[9] <= '7') {
+    if (!(value > 0.0) || value > 100.0) return DK_ERR_INVALID;
+    c.xcd_speed[key[9] - '0'] = (float)value;
+    return DK_OK;
+  }
+  return DK_ERR_UNSUPPORTED;
 }
 
 int32_t dk_seq_acquire(dk_pool* pool, int32_t region, int64_t timeout_ms, int32_t* slot_out) {
@@ -207,96 +261,118 @@ int32_t dk_pool_stats(dk_pool* pool, int64_t* held, int64_t* free_cells) {
 int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
                      const int32_t* n_accept, const void* k_new, const void* v_new, void* stream) {
   if (!pool) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> launch(pool->launch_mu);
-  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
-  if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
-  std::vector<int64_t> dst;
-  int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst);
-  if (rc != DK_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  if (total <= dk::KV_INLINE_MAX_TOKENS) {
-    hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
-                                                (int32_t)total, k_new, v_new, st);
-    return e == hipSuccess ? DK_OK : pool->hip_fail(e);
-  }
-  const int64_t per_launch = pool->desc.dev_meta_bytes / (int64_t)sizeof(int32_t);
-  for (int64_t base = 0; base < total; base += per_launch) {
-    const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);
-    Staging* s;
-    rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> launch(pool->launch_mu);
+    const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+    if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
+    const bool inline_cells = total <= dk::KV_INLINE_MAX_TOKENS;
+    const int64_t per_launch =
+        std::min<int64_t>(pool->desc.dev_meta_bytes, (int64_t)pool->stage_cap) / (int64_t)sizeof(int32_t);
+    if (!inline_cells && per_launch <= 0) return DK_ERR_WORKSPACE;  // long appends need staging memory
+    std::vector<int64_t> dst, old_len;
+    int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst, &old_len);
     if (rc != DK_OK) return rc;
-    int32_t* h = (int32_t*)s->host;
-    for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)dst[base + t];
-    rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
-    if (rc != DK_OK) return rc;
-    hipError_t e = dk::launch_kv_scatter(pool->view(), pool->desc.k_arena, pool->desc.v_arena,
-                                         (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
-  }
-  return DK_OK;
+    // From here on a failure must leave the pool as it was: the bookkeeping is rolled back.
+    const auto undo = [&](int32_t status) {
+      for (int32_t b = 0; b < n_seqs; ++b) (void)pool->meta.trim(slots[b], old_len[b]);
+      return status;
+    };
+    hipStream_t st = (hipStream_t)stream;
+    if (inline_cells) {
+      hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
+                                                  (int32_t)total, k_new, v_new, st);
+      return e == hipSuccess ? DK_OK : undo(pool->hip_fail(e));
+    }
+    for (int64_t base = 0; base < total; base += per_launch) {
+      const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);
+      Staging* s;
+      rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+      // Chunks already enqueued wrote cells that the rolled-back slots no longer own: harmless, they are free.
+      if (rc != DK_OK) return undo(rc);
+      int32_t* h = (int32_t*)s->host;
+      for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)dst[base + t];
+      rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+      if (rc != DK_OK) return undo(rc);
+      hipError_t e = dk::launch_kv_scatter(pool->view(), pool->desc.k_arena, pool->desc.v_arena,
+                                           (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
+      if (e != hipSuccess) return undo(pool->hip_fail(e));
+    }
+    return DK_OK;
+  });
 }
 
 int32_t dk_kv_reserve(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
                       const int32_t* n_accept, int64_t* cells_out) {
   if (!pool) return DK_ERR_INVALID;
-  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
-  if (total > 0 && !cells_out) return DK_ERR_INVALID;
-  std::vector<int64_t> dst;
-  int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst);
-  if (rc != DK_OK) return rc;
-  for (int64_t t = 0; t < total; ++t) cells_out[t] = dst[t];
-  return DK_OK;
+  return guarded([&]() -> int32_t {
+    const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+    if (total > 0 && !cells_out) return DK_ERR_INVALID;
+    std::vector<int64_t> dst;
+    int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst, nullptr);
+    if (rc != DK_OK) return rc;
+    for (int64_t t = 0; t < total; ++t) cells_out[t] = dst[t];
+    return DK_OK;
+  });
 }
 
 int32_t dk_seq_gather(dk_pool* pool, int32_t slot, void* k_out, void* v_out, void* stream) {
   if (!pool) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> launch(pool->launch_mu);
-  int64_t len = 0;
-  int32_t rc = pool->meta.length(slot, &len);
-  if (rc != DK_OK) return rc;
-  if (len == 0) return DK_OK;
-  if (!k_out || !v_out) return DK_ERR_INVALID;
-  std::vector<int64_t> cells(len);
-  rc = pool->meta.cells(slot, cells.data(), len);
-  if (rc != DK_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  const int64_t per_launch = pool->desc.dev_meta_bytes / (int64_t)sizeof(int32_t);
-  for (int64_t base = 0; base < len; base += per_launch) {
-    const int32_t n = (int32_t)std::min<int64_t>(per_launch, len - base);
-    Staging* s;
-    rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> launch(pool->launch_mu);
+    int64_t len = 0;
+    int32_t rc = pool->meta.length(slot, &len);
     if (rc != DK_OK) return rc;
-    int32_t* h = (int32_t*)s->host;
-    for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)cells[base + t];
-    rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+    if (len == 0) return DK_OK;
+    if (!k_out || !v_out) return DK_ERR_INVALID;
+    std::vector<int64_t> cells(len);
+    rc = pool->meta.cells(slot, cells.data(), len);
     if (rc != DK_OK) return rc;
-    hipError_t e = dk::launch_kv_gather(pool->view(), (const int32_t*)pool->desc.dev_meta, base, n, k_out, v_out, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
-  }
-  return DK_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t per_launch =
+        std::min<int64_t>(pool->desc.dev_meta_bytes, (int64_t)pool->stage_cap) / (int64_t)sizeof(int32_t);
+    if (per_launch <= 0) return DK_ERR_WORKSPACE;
+    for (int64_t base = 0; base < len; base += per_launch) {
+      const int32_t n = (int32_t)std::min<int64_t>(per_launch, len - base);
+      Staging* s;
+      rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+      if (rc != DK_OK) return rc;
+      int32_t* h = (int32_t*)s->host;
+      for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)cells[base + t];
+      rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+      if (rc != DK_OK) return rc;
+      hipError_t e = dk::launch_kv_gather(pool->view(), (const int32_t*)pool->desc.dev_meta, base, n, k_out, v_out, st);
+      if (e != hipSuccess) return pool->hip_fail(e);
+    }
+    return DK_OK;
+  });
 }
 
 int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
                                   int32_t staged, int64_t* bytes_out) {
   if (!pool || !bytes_out) return DK_ERR_INVALID;
-  dk::AttendPlan plan;
-  dk::PlanConfig cfg = pool->cfg;
-  if (pool->variant == 1) cfg.use_mfma = false;
-  std::lock_guard<std::mutex> lk(pool->meta.mutex());
-  int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged != 0, &plan);
-  if (rc != DK_OK) return rc;
-  *bytes_out = (int64_t)plan.total_bytes;
-  return DK_OK;
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> launch(pool->launch_mu);
+    dk::AttendPlan& plan = pool->plan;
+    dk::PlanConfig cfg = pool->cfg;
+    if (pool->variant == 1) cfg.use_mfma = false;
+    std::lock_guard<std::mutex> lk(pool->meta.mutex());
+    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged != 0, &plan);
+    if (rc != DK_OK) return rc;
+    *bytes_out = (int64_t)plan.total_bytes;
+    return DK_OK;
+  });
 }
 
-int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
-                        const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
-                        int64_t workspace_bytes, void* stream) {
-  if (!pool) return DK_ERR_INVALID;
+namespace {
+
+// Plans the call, uploads its descriptors into `workspace` and launches the attention kernels.
+int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                    const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                    int64_t workspace_bytes, void* stream) {
   if ((k_new == nullptr) != (v_new == nullptr)) return DK_ERR_INVALID;
   std::lock_guard<std::mutex> launch(pool->launch_mu);
   const bool staged = k_new != nullptr;
-  dk::AttendPlan plan;
+  dk::AttendPlan& plan = pool->plan;
   dk::PlanConfig cfg = pool->cfg;
   // the MFMA kernels take the row maximum before scaling, which needs a positive finite scale
   if (pool->variant == 1 || !(scale > 0.f) || !(scale < 3.0e38f)) cfg.use_mfma = false;
@@ -313,7 +389,7 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
   Staging* s;
   int32_t rc = pool->stage(plan.blob_bytes, &s);
   if (rc != DK_OK) return rc;
-  char* h = (char*)s->host;
+  char* h = s->host;
   auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
   put(plan.off_entries, plan.entries.data(), plan.entries.size() * sizeof(DkEntry));
   put(plan.off_segs, plan.segs.data(), plan.segs.size() * sizeof(DkSeg));
@@ -357,19 +433,29 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
     e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (const int32_t*)(ws + plan.off_links),
                                  plan.stream_chains, stream_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
-  }
-  if (timing) {
-    e = hipEventRecord(pool->ev1[ev_slot], st);
-    if (e != hipSuccess) return pool->hip_fail(e);
-    ++pool->ev_calls;
-  }
-  if (cfg.use_mfma) {
     int32_t max_rows = 0;
     for (const DkMerge& mg : plan.merges) max_rows = std::max(max_rows, mg.nrows);
     e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), max_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
+  if (timing) {  // the interval covers every kernel of the call, the merge of split key ranges included
+    e = hipEventRecord(pool->ev1[ev_slot], st);
+    if (e != hipSuccess) return pool->hip_fail(e);
+    ++pool->ev_calls;
+  }
   return DK_OK;
+}
+
+}  // namespace
+
+int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                        const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                        int64_t workspace_bytes, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  return guarded([&]() -> int32_t {
+    return attend_impl(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, workspace, workspace_bytes,
+                       stream);
+  });
 }
 
 }  // extern "C"
@@ -385,8 +471,10 @@ extern "C" {
 
 int32_t dk_radix_create(dk_pool* pool, int64_t cell_budget, int32_t keep_last, dk_radix** radix_out) {
   if (!pool || !radix_out || cell_budget <= 0 || keep_last < 0) return DK_ERR_INVALID;
-  *radix_out = new (std::nothrow) dk_radix(pool, cell_budget, keep_last);
-  return *radix_out ? DK_OK : DK_ERR_INVALID;
+  return guarded([&]() -> int32_t {
+    *radix_out = new dk_radix(pool, cell_budget, keep_last);
+    return DK_OK;
+  });
 }
 int32_t dk_radix_destroy(dk_radix* radix) {
   if (!radix) return DK_ERR_INVALID;
@@ -396,13 +484,17 @@ int32_t dk_radix_destroy(dk_radix* radix) {
 int32_t dk_radix_begin_turn(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens,
                             int64_t* n_past_out) {
   if (!radix) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(radix->mu);
-  return radix->trie.begin_turn(slot, tokens, n_tokens, n_past_out);
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> lk(radix->mu);
+    return radix->trie.begin_turn(slot, tokens, n_tokens, n_past_out);
+  });
 }
 int32_t dk_radix_save(dk_radix* radix, int32_t slot, const int32_t* tokens, int64_t n_tokens, int32_t* saved_out) {
   if (!radix) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> lk(radix->mu);
-  return radix->trie.save(slot, tokens, n_tokens, saved_out);
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> lk(radix->mu);
+    return radix->trie.save(slot, tokens, n_tokens, saved_out);
+  });
 }
 int32_t dk_radix_stats(dk_radix* radix, int64_t* nodes_out, int64_t* cells_out, int64_t* donors_out,
                        int64_t* evictions_out) {
@@ -457,21 +549,28 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant) {
 
 int32_t dk_set_attend_timing(dk_pool* pool, int32_t n_calls) {
   if (!pool || n_calls < 0 || n_calls > 256) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> launch(pool->launch_mu);
-  for (hipEvent_t e : pool->ev0) (void)hipEventDestroy(e);
-  for (hipEvent_t e : pool->ev1) (void)hipEventDestroy(e);
-  pool->ev0.clear();
-  pool->ev1.clear();
-  pool->ev_calls = 0;
-  for (int32_t i = 0; i < n_calls; ++i) {
-    hipEvent_t a = nullptr, b = nullptr;
-    hipError_t e = hipEventCreate(&a);
-    if (e == hipSuccess) e = hipEventCreate(&b);
-    if (e != hipSuccess) return pool->hip_fail(e);
-    pool->ev0.push_back(a);
-    pool->ev1.push_back(b);
-  }
-  return DK_OK;
+  return guarded([&]() -> int32_t {
+    std::lock_guard<std::mutex> launch(pool->launch_mu);
+    pool->ev0.reserve(256);  // so that the push_backs below cannot throw half-way
+    pool->ev1.reserve(256);
+    for (hipEvent_t e : pool->ev0) (void)hipEventDestroy(e);
+    for (hipEvent_t e : pool->ev1) (void)hipEventDestroy(e);
+    pool->ev0.clear();
+    pool->ev1.clear();
+    pool->ev_calls = 0;
+    for (int32_t i = 0; i < n_calls; ++i) {
+      hipEvent_t a = nullptr, b = nullptr;
+      hipError_t e = hipEventCreate(&a);
+      if (e == hipSuccess) e = hipEventCreate(&b);
+      if (e != hipSuccess) {
+        if (a) (void)hipEventDestroy(a);
+        return pool->hip_fail(e);
+      }
+      pool->ev0.push_back(a);
+      pool->ev1.push_back(b);
+    }
+    return DK_OK;
+  });
 }
 
 int32_t dk_attend_times(dk_pool* pool, float* ms_out, int32_t cap, int32_t* n_out) {
@@ -507,6 +606,8 @@ const char* dk_strerror(int32_t status) {
     case DK_ERR_UNSUPPORTED: return "unsupported shape, dtype or alias form";
     case DK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case DK_ERR_HIP: return "HIP runtime error";
+    case DK_ERR_BUSY: return "every staging buffer is still in flight: synchronise the stream and call again";
+    case DK_ERR_NO_MEMORY: return "out of host memory";
     default: return "unknown status";
   }
 }

@@ -17,6 +17,8 @@
 // reads (ds_read_b64_tr_b16, 4 rows x 16 columns per 16 lanes) are bank-conflict free.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "attend_common.hpp"
 #include "kernels.hpp"
 
@@ -291,16 +293,17 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const 
   using namespace mfma;
   if (n_chains <= 0) return hipSuccess;
   if (a.arena.head_dim != D || a.arena.dtype != 1 || max_rows > 64) return hipErrorInvalidValue;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_stream_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       STREAM_LDS_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)attend_stream_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              STREAM_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  // once per process, whatever thread or pool gets here first
+  static std::once_flag attr_once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(attr_once, [] {
+    attr_status = hipFuncSetAttribute((const void*)attend_stream_kernel<1>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
+    if (attr_status == hipSuccess)
+      attr_status = hipFuncSetAttribute((const void*)attend_stream_kernel<2>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const Ctx c = make_ctx(a, items);
   if (max_rows <= 32)
     attend_stream_kernel<1><<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);

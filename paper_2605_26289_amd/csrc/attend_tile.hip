@@ -34,6 +34,8 @@
 // allocates; the consequence is that MFMA-result hazards are handled by hand (see settle()).
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include <utility>
 
 #include "attend_common.hpp"
@@ -631,13 +633,14 @@ hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t 
   using namespace mfma;
   if (n_items <= 0) return hipSuccess;
   if (a.arena.head_dim != D || a.arena.dtype != 1) return hipErrorInvalidValue;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attend_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       TILE_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  // once per process, whatever thread or pool gets here first
+  static std::once_flag attr_once;
+  static hipError_t attr_status = hipSuccess;
+  std::call_once(attr_once, [] {
+    attr_status = hipFuncSetAttribute((const void*)attend_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      TILE_LDS_BYTES);
+  });
+  if (attr_status != hipSuccess) return attr_status;
   const Ctx c = make_ctx(a, items);
   attend_tile_kernel<<<dim3((unsigned)n_items * a.arena.n_kv_heads), 256, TILE_LDS_BYTES, stream>>>(c);
   return hipGetLastError();

@@ -9,9 +9,8 @@ namespace dk {
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 namespace {
-struct RowTile {
-  int32_t entry, row0, nrows, kv_hi;
-};
+typedef PlanRowTile RowTile;
+typedef PlanKeyedItem Keyed;
 
 // Splits each row tile's visible key range [0, kv_hi) into chunks so that the items of one kernel
 // have similar cost and there are about `target` of them per KV head.  All row tiles of an entry use
@@ -19,7 +18,8 @@ struct RowTile {
 // read the same K/V tiles, so they are made neighbours in launch order (`group` = true) and, running
 // at the same time on the XCD of their KV head, fetch each tile from HBM once and from L2 after that.
 void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk, bool group,
-               int32_t wave_slots, std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
+               int32_t wave_slots, std::vector<Keyed>& keyed, std::vector<int64_t>& cost, std::vector<DkItem>* items,
+               std::vector<DkMerge>* merges, int64_t* part_rows) {
   if (tiles.empty()) return;
   int64_t total = 0;
   int32_t longest = 0;
@@ -60,12 +60,7 @@ void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t targe
     if (best_chunk) chunk = best_chunk;
   }
 
-  struct Keyed {
-    DkItem it;
-    int64_t group_cost;
-    int32_t split;
-  };
-  std::vector<Keyed> keyed;
+  keyed.clear();
   // tiles of one entry are consecutive in `tiles`
   for (size_t b = 0; b < tiles.size();) {
     size_t e = b;
@@ -98,7 +93,7 @@ void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t targe
       }
     }
     // cost of each (entry, chunk) group
-    std::vector<int64_t> cost(nsplit + 1, 0);
+    cost.assign((size_t)nsplit + 1, 0);
     for (size_t k = first; k < keyed.size(); ++k)
       cost[keyed[k].split] += (int64_t)(keyed[k].it.kv_hi - keyed[k].it.kv_lo) * keyed[k].it.nrows;
     for (size_t k = first; k < keyed.size(); ++k) keyed[k].group_cost = cost[keyed[k].split];
@@ -127,8 +122,8 @@ void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t targe
 // idle chains the faster ones are served first, so they get the longest units), so that all compute
 // units finish together whatever the mix of context lengths.  With very many small units, runs of
 // consecutive units are handed out as one block to keep the planning time down.
-void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::vector<int32_t>* links,
-                 int32_t* n_chains) {
+void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::vector<std::pair<double, int32_t>>& heap,
+                 std::vector<int32_t>& tail, std::vector<int32_t>* links, int32_t* n_chains) {
   const int64_t n_units = (int64_t)items.size() * cfg.n_kv_heads;
   const int32_t chains = (int32_t)std::min<int64_t>(n_units, std::max(cfg.stream_chains, 1));
   *n_chains = chains;
@@ -142,11 +137,11 @@ void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::v
   double inv_speed[8];
   for (int x = 0; x < 8; ++x) inv_speed[x] = 1.0 / (cfg.xcd_speed[x] > 0.f ? cfg.xcd_speed[x] : 1.f);
   typedef std::pair<double, int32_t> Free;  // (time at which the chain is free, chain)
-  std::vector<Free> heap((size_t)chains);
+  heap.resize((size_t)chains);
   for (int32_t c = 0; c < chains; ++c) heap[c] = {1e-6 * inv_speed[c & 7], c};
   const auto later = [](const Free& a, const Free& b) { return a > b; };
   std::make_heap(heap.begin(), heap.end(), later);
-  std::vector<int32_t> tail((size_t)chains, -1);
+  tail.assign((size_t)chains, -1);
   const int64_t per_block = (n_units + 8 * (int64_t)chains - 1) / (8 * (int64_t)chains);
   for (int64_t u0 = 0; u0 < n_units; u0 += per_block) {
     const int64_t u1 = std::min(n_units, u0 + per_block);
@@ -170,11 +165,21 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
                    bool staged, AttendPlan* p) {
   int32_t rc = pool.check_batch(n_seqs, slots, cu_delta);
   if (rc != OK) return rc;
-  *p = AttendPlan();
+  p->entries.clear();
+  p->segs.clear();
+  p->tile_items.clear();
+  p->stream_items.clear();
+  p->merges.clear();
+  p->stream_links.clear();
+  p->stream_chains = 0;
+  p->part_rows = 0;
   p->total_tokens = n_seqs ? cu_delta[n_seqs] : 0;
   const int32_t group = cfg.n_q_heads / cfg.n_kv_heads;
-  std::vector<Extent> ext;
-  std::vector<RowTile> tile_tiles, stream_tiles;
+  std::vector<Extent>& ext = p->ext;
+  std::vector<RowTile>& tile_tiles = p->tile_tiles;
+  std::vector<RowTile>& stream_tiles = p->stream_tiles;
+  tile_tiles.clear();
+  stream_tiles.clear();
   for (int32_t b = 0; b < n_seqs; ++b) {
     const int32_t delta = cu_delta[b + 1] - cu_delta[b];
     int64_t len = 0;
@@ -206,11 +211,11 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
       }
     }
   }
-  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, &p->tile_items,
-            &p->merges, &p->part_rows);
-  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, &p->stream_items,
-            &p->merges, &p->part_rows);
-  chain_units(p->stream_items, cfg, &p->stream_links, &p->stream_chains);
+  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, p->keyed, p->cost,
+            &p->tile_items, &p->merges, &p->part_rows);
+  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, p->keyed, p->cost,
+            &p->stream_items, &p->merges, &p->part_rows);
+  chain_units(p->stream_items, cfg, p->heap, p->tail, &p->stream_links, &p->stream_chains);
 
   size_t off = 0;
   p->off_entries = off;

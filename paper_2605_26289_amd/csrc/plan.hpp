@@ -4,6 +4,7 @@
 #pragma once
 #include <cstddef>
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 #include "device_types.h"
@@ -26,7 +27,27 @@ struct PlanConfig {
   float xcd_speed[8];        // relative K/V streaming rate of the XCD that workgroup w lands on (w % 8)
 };
 
+// One packed row tile of an entry before its key range is cut: rows [row0, row0 + nrows) see keys [0, kv_hi).
+struct PlanRowTile {
+  int32_t entry, row0, nrows, kv_hi;
+};
+struct PlanKeyedItem {
+  DkItem it;
+  int64_t group_cost;
+  int32_t split;
+};
+
+// A plan object may be reused from call to call: build_plan() clears it but keeps the capacity of its
+// vectors, so that planning a batch like the previous one allocates nothing.
 struct AttendPlan {
+  // working storage of build_plan
+  std::vector<Extent> ext;
+  std::vector<PlanRowTile> tile_tiles, stream_tiles;
+  std::vector<PlanKeyedItem> keyed;
+  std::vector<int64_t> cost;
+  std::vector<std::pair<double, int32_t>> heap;
+  std::vector<int32_t> tail;
+
   std::vector<DkEntry> entries;
   std::vector<DkSeg> segs;
   std::vector<DkItem> tile_items, stream_items;

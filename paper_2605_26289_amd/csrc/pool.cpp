@@ -262,7 +262,7 @@ int32_t Pool::check_batch(int32_t n_seqs, const int32_t* slots, const int32_t* c
 }
 
 int32_t Pool::append(int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const int32_t* n_accept,
-                     std::vector<int64_t>* dst_cell) {
+                     std::vector<int64_t>* dst_cell, std::vector<int64_t>* old_len) {
   std::lock_guard<std::mutex> lk(mu_);
   int32_t rc = check_batch(n_seqs, slots, cu_delta);
   if (rc != OK) return rc;
@@ -277,6 +277,10 @@ int32_t Pool::append(int32_t n_seqs, const int32_t* slots, const int32_t* cu_del
   }
   if (need > alloc_.free_count()) return ERR_NO_CELLS;
   dst_cell->assign(total, -1);
+  if (old_len) {
+    old_len->resize((size_t)n_seqs);
+    for (int32_t b = 0; b < n_seqs; ++b) (*old_len)[b] = slots_[slots[b]].len;
+  }
   for (int32_t b = 0; b < n_seqs; ++b) {
     const int64_t delta = cu_delta[b + 1] - cu_delta[b];
     const int64_t cnt = n_accept ? n_accept[b] : delta;

@@ -99,10 +99,10 @@ class Pool {
   int32_t stats(int64_t* held, int64_t* free_cells);
 
   // Batched append bookkeeping: checks every slot, reserves the cells, advances the lengths and
-  // reports the destination cell of every appended token (dst[t] = -1 for tokens not appended).
-  // All or nothing.
+  // reports the destination cell of every appended token (dst[t] = -1 for tokens not appended) and,
+  // if asked, every slot's length before the call.  All or nothing.
   int32_t append(int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const int32_t* n_accept,
-                 std::vector<int64_t>* dst_cell);
+                 std::vector<int64_t>* dst_cell, std::vector<int64_t>* old_len = nullptr);
 
   // Logical view of a slot as merged extents, positions ascending.
   int32_t extents(int32_t slot, std::vector<Extent>* out, int64_t* len_out);

@@ -29,11 +29,16 @@ class DevicePool:
         self.v_arena = torch.empty_like(self.k_arena)
         desc = dk.PoolDesc(n_slots, n_session_slots, arena_cells, granule_cells, n_q_heads, n_kv_heads, head_dim,
                            dk.BF16 if dtype == "bf16" else dk.F32, self.k_arena.data_ptr(), self.v_arena.data_ptr(),
-                           None, 0)
+                           None, 0, None, 0, 0)
         nbytes = dk.meta_bytes(desc)
         self.dev_meta = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         desc.dev_meta = self.dev_meta.data_ptr()
         desc.dev_meta_bytes = nbytes
+        # pinned staging memory for descriptor uploads: allocated here, once, never by a launching call
+        self.host_staging = torch.empty(dk.staging_bytes(desc) + 256, dtype=torch.uint8, pin_memory=True)
+        base = self.host_staging.data_ptr()
+        desc.host_staging = (base + 255) // 256 * 256
+        desc.host_staging_bytes = dk.staging_bytes(desc)
         self.handle = dk.pool_create(desc)
         self.workspace: Optional[torch.Tensor] = None
 

@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_every_status_code_has_its_own_message():
-    codes = [0] + list(range(-1, -9, -1))
+    codes = [0] + list(range(-1, -11, -1))
     texts = [dk.strerror(c) for c in codes]
     assert all(t and "unknown" not in t.lower() for t in texts) and len(set(texts)) == len(texts)
     assert "unknown" in dk.strerror(-99).lower() or dk.strerror(-99) not in texts
@@ -44,7 +44,8 @@ def test_every_status_code_has_its_own_message():
 def test_create_rejects_bad_descriptions():
     def rc(**kw):
         base = dict(n_slots=2, n_session_slots=0, arena_cells=512, granule_cells=16, n_q_heads=8, n_kv_heads=2,
-                    head_dim=64, dtype=dk.BF16, k_arena=256, v_arena=512, dev_meta=768, dev_meta_bytes=1 << 20)
+                    head_dim=64, dtype=dk.BF16, k_arena=256, v_arena=512, dev_meta=768, dev_meta_bytes=1 << 20,
+                    host_staging=None, host_staging_bytes=0, staging_depth=0)
         base.update(kw)
         d = dk.PoolDesc(*[base[f[0]] for f in dk.PoolDesc._fields_])
         out = C.c_void_p()
@@ -62,6 +63,38 @@ def test_create_rejects_bad_descriptions():
     assert rc(k_arena=257) == "INVALID"
     assert rc(dev_meta_bytes=16) == "INVALID"
     assert rc(arena_cells=8) == "INVALID"
+    assert rc(host_staging_bytes=1 << 20) == "INVALID"          # bytes without memory
+    assert rc(host_staging=4096) == "INVALID"                   # memory without bytes
+    assert rc(host_staging=4097, host_staging_bytes=8 << 20) == "INVALID"   # misaligned
+    assert rc(host_staging=4096, host_staging_bytes=8 << 10) == "INVALID"   # buffers below 64 KiB
+    assert rc(staging_depth=65) == "INVALID"
+
+
+def test_tuning_names_and_ranges_and_no_environment_channel(monkeypatch):
+    monkeypatch.setenv("DELTAKV_STREAM_CHAINS", "3")  # the library reads no environment variable
+    p = _pool()
+    dk.set_tuning(p, "stream_chains", 128)
+    dk.set_tuning(p, "xcd_speed3", 0.93)
+    for name, value, err in (("stream_chains", 0, "INVALID"), ("stream_chains", 1.5, "INVALID"),
+                             ("xcd_speed8", 1.0, "UNSUPPORTED"), ("xcd_speed0", 0.0, "INVALID"),
+                             ("no_such_knob", 1, "UNSUPPORTED"), ("tile_min_chunk", 8, "INVALID")):
+        with pytest.raises(dk.DeltaKVError) as e:
+            dk.set_tuning(p, name, value)
+        assert e.value.name == err, (name, value)
+    dk.pool_destroy(p)
+
+
+def test_launching_calls_without_staging_memory_report_workspace():
+    """A pool created for host-only use (no staging memory): an append too long for the in-argument cell table
+    fails before it touches any state."""
+    p = _pool(arena_cells=1 << 14)
+    s = dk.seq_acquire(p, 0)
+    with pytest.raises(dk.DeltaKVError) as e:
+        dk._check(dk.lib().dk_kv_append(p, 1, (C.c_int32 * 1)(s), (C.c_int32 * 2)(0, 2000), None, 256, 256, None),
+                  "kv_append")
+    assert e.value.name == "WORKSPACE"
+    assert dk.seq_len(p, s) == 0 and dk.pool_stats(p)[0] == 0
+    dk.pool_destroy(p)
 
 
 def test_regions_timeout_and_blocking_acquire():
