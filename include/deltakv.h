@@ -182,6 +182,24 @@ int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, con
                         int64_t workspace_bytes, void* stream);
 
 /*
+ * delta_attend for callers that cannot allocate and have no workspace to hand over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * dk_delta_attend without the workspace pair: the call's descriptors and split partials live in an array of
+ * DK_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the library runs on holds its
+ * copy until the process ends).  The call allocates no device or pinned memory.  A batch that needs more than
+ * DK_STATIC_SCRATCH_BYTES -- dk_attend_workspace_bytes() says how much it needs -- returns DK_ERR_WORKSPACE
+ * and launches nothing: decode and verification batches need tens of KiB, prefill turns whose key range is
+ * split need (splits x packed rows x KV heads x 520) bytes on top.
+ * All calls on one GPU share that GPU's array, whatever pool they use: calls that may overlap on the device
+ * (different streams without an ordering between them) race.  Nothing has to be cleared between calls: every
+ * byte a call reads from the array it has written itself.
+ */
+#define DK_STATIC_SCRATCH_BYTES (32 << 20)
+int32_t dk_delta_attend_noalloc(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                                const void* q, const void* k_new, const void* v_new, float scale, void* out,
+                                float* lse, void* stream);
+
+/*
  * verify_greedy: the step after the Delta = k+1 verification pass of paper Alg. 2, on the device
  * (Sec. 3.8: greedy sampling is an argmax over the vocabulary logits, batched over the k+1
  * speculated positions, and the host never scans the logits).  Slot b's batch rows

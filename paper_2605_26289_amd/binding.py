@@ -58,6 +58,8 @@ SIGNATURES = {
     "dk_attend_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_int32, _I64P]),
     "dk_delta_attend": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
+    "dk_delta_attend_noalloc": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
     "dk_seq_gather": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_pool_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P]),
@@ -242,6 +244,19 @@ def delta_attend(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=
     _launch(lambda: lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new),
                                           float(scale), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, st),
             "delta_attend", pool, stream)
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def delta_attend_noalloc(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=None, lse=None,
+                         stream=None) -> None:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    st = _stream(stream)
+    _launch(lambda: lib().dk_delta_attend_noalloc(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                  float(scale), _ptr(out), _ptr(lse), st),
+            "delta_attend_noalloc", pool, stream)
 
 
 def verify_workspace_bytes(total_rows: int, vocab: int, dtype: int) -> int:

@@ -448,6 +448,51 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
 
 }  // namespace
 
+namespace {
+
+// Scratch of dk_delta_attend_noalloc: descriptors and split partials of one call.  Every GPU the library
+// runs on holds its own copy of this array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[DK_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, resolved on first use
+std::mutex g_scratch_mu;
+
+// The array's name is only a host-side handle; what kernels and copies need is the address the current
+// device gave its copy of the array.
+int32_t static_scratch(dk_pool* pool, void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return pool->hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return DK_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return pool->hip_fail(e);
+    if (!ptr) return pool->hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DK_OK;
+}
+
+}  // namespace
+
+int32_t dk_delta_attend_noalloc(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                                const void* q, const void* k_new, const void* v_new, float scale, void* out,
+                                float* lse, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  return guarded([&]() -> int32_t {
+    void* ws = nullptr;
+    const int32_t rc = static_scratch(pool, &ws);
+    if (rc != DK_OK) return rc;
+    // a call that needs more than the array holds is turned down by the size check (DK_ERR_WORKSPACE)
+    return attend_impl(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, ws,
+                       (int64_t)DK_STATIC_SCRATCH_BYTES, stream);
+  });
+}
+
 int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
                         const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
                         int64_t workspace_bytes, void* stream) {
