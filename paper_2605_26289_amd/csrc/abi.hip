@@ -195,6 +195,7 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
     c.stream_target = std::max(1, 256 / desc->n_kv_heads);
     c.tile_wave_slots = std::max(1, 256 / desc->n_kv_heads);
     c.tile_min_chunk = 128;
+    c.tile_item_cost = 3;
     c.stream_min_chunk = 512;
     c.stream_chains = 256;
     c.stream_item_cost = 512;
@@ -229,6 +230,7 @@ int32_t dk_set_tuning(dk_pool* pool, const char* name, double value) {
   if (key == "stream_item_cost") return whole(0, 1 << 20, &c.stream_item_cost);
   if (key == "tile_wave_slots") return whole(1, 1 << 16, &c.tile_wave_slots);
   if (key == "tile_min_chunk") return whole(64, 1 << 24, &c.tile_min_chunk);
+  if (key == "tile_item_cost") return whole(0, 1 << 16, &c.tile_item_cost);
   if (key.size() == 10 && key.compare(0, 9, "xcd_speed") == 0 && key[9] >= '0' && key[9] <= '7') {
     if (!(value > 0.0) || value > 100.0) return DK_ERR_INVALID;
     c.xcd_speed[key[9] - '0'] = (float)value;
@@ -394,6 +396,7 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   put(plan.off_entries, plan.entries.data(), plan.entries.size() * sizeof(DkEntry));
   put(plan.off_segs, plan.segs.data(), plan.segs.size() * sizeof(DkSeg));
   put(plan.off_tile, plan.tile_items.data(), plan.tile_items.size() * sizeof(DkItem));
+  put(plan.off_tile_links, plan.tile_links.data(), plan.tile_links.size() * sizeof(int32_t));
   put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
   put(plan.off_links, plan.stream_links.data(), plan.stream_links.size() * sizeof(int32_t));
   put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
@@ -426,7 +429,8 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
     e = dk::launch_attend_ref(a, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   } else {
-    e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (int32_t)plan.tile_items.size(), st);
+    e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (const int32_t*)(ws + plan.off_tile_links),
+                               plan.tile_chains, st);
     if (e != hipSuccess) return pool->hip_fail(e);
     int32_t stream_rows = 0;
     for (const DkItem& it : plan.stream_items) stream_rows = std::max(stream_rows, it.nrows);

@@ -35,7 +35,6 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
-
 #include <utility>
 
 #include "attend_common.hpp"
@@ -101,6 +100,16 @@ __device__ unsigned long long g_prof[8];
 #else
 #define DK_PROF_T(x)
 #define DK_PROF_ADD(i, v)
+#endif
+
+#ifdef DK_TRACE  // timeline build: wall-clock stamps (100 MHz) of wavefront 0 per workgroup and item
+__device__ unsigned long long g_trace[256][16][8];
+#define DK_TR(seq, ph)                                                                                  \
+  do {                                                                                                  \
+    if (threadIdx.x == 0 && (seq) < 16 && blockIdx.x < 256) g_trace[blockIdx.x][(seq)][(ph)] = wall_clock64(); \
+  } while (0)
+#else
+#define DK_TR(seq, ph)
 #endif
 
 struct WaveState {
@@ -361,36 +370,17 @@ __device__ __forceinline__ void plain_s(const char* k_lds, const bf16x8 (&qf)[MB
   settle(s[0][0], s[0][1], s[1][0], s[1][1]);
 }
 
-__global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
+// grid = n_chains * n_kv_heads workgroups, at most one per compute unit: workgroup w serves KV head
+// w % n_kv_heads (with 8 KV heads that is also the XCD it lands on, so all row tiles of a head share one
+// L2) and walks chain w / n_kv_heads of work items: links[chain], links[n_chains + item], ... until a
+// link is negative.  The chains are the same for every KV head; the planner balanced them.
+// Between two items of a chain the loads of the next item (descriptors, Q, its first two K/V tiles) are
+// requested before the output of the finished one is stored, so they overlap with the store phase.
+__global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_t* links, int n_chains) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int g = blockIdx.x % c.n_kv_heads;
-  const DkItem it = load_desc(c.items, blockIdx.x / c.n_kv_heads);
-  const DkEntry e = load_desc(c.entries, it.entry);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int last_row = it.row0 + it.nrows - 1;
-  const int wave_row0 = it.row0 + wave * (MB * 32);
-  const bool wave_active = wave_row0 <= last_row;
-  const int wave_min_limit = e.n + (min(wave_row0, last_row) >> c.gshift);
-  // keys at positions above this are invisible to every row of the wavefront: those tiles are skipped
-  const int wave_max_limit = wave_active ? e.n + (min(wave_row0 + MB * 32 - 1, last_row) >> c.gshift) : -1;
-
-  bf16x8 qf[MB][8];
-  int limit[MB];
-  load_q<MB>(c, e, g, wave_row0, last_row, lane, qf, limit);  // waited for below, after the first K/V requests
-
-  WaveState st;
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    st.m[mb] = -INFINITY;
-    st.l[mb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      f32x16 z = {0};
-      asm volatile("" : "+a"(z));  // born in an AGPR tuple as a whole
-      st.o[db][mb] = z;
-    }
-  }
   const uint32_t koff = k_lane_off(lane), voff = v_lane_off(lane);
 
   // Two LDS rings of 16 KiB stages: K tile u lives in stage u % 3 of the K ring, V tile u in stage
@@ -404,11 +394,22 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
   char* const v_ring = smem + TILE_K_RING * TILE_STAGE_BYTES;
   const uint32_t k_ring_lds = (uint32_t)(uintptr_t)(lds_void_ptr)k_ring + wave * 1024;
   const uint32_t v_ring_lds = (uint32_t)(uintptr_t)(lds_void_ptr)v_ring + wave * 1024;
-  KvCursor cur{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
+
+  // ---- state of the item being worked on (set by begin_item) -------------------------------------
+  DkItem it;
+  DkEntry e;
+  int last_row = 0, wave_min_limit = 0, wave_max_limit = -1;
+  bool wave_active = false;
+  bf16x8 qf[MB][8];
+  int limit[MB];
+  KvCursor cur{c.segs, 0, 0, 0, 0};
   KvTile tl;  // next tile to load
   TileLoads ld;
   int ld_cnt = -1;
   uint32_t ld_stride = 0;
+  // (cnt, pos) of tiles t .. t+2 of the step about to run; cnt 0 = no such tile
+  int cnt0 = 0, pos0 = 0, cnt1 = 0, pos1 = 0, cnt2 = 0, pos2 = 0;
+
   auto offsets_stale = [&]() { return tl.cnt != ld_cnt || tl.stride != ld_stride; };
   auto refresh_offsets = [&]() {
     ld_cnt = tl.cnt;
@@ -433,205 +434,274 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c) {
     issue_one<7>(ld);
   };
 
-  // (cnt, pos) of tiles t .. t+2 of the step about to run; cnt 0 = no such tile
-  int cnt0 = 0, pos0 = 0, cnt1 = 0, pos1 = 0, cnt2 = 0, pos2 = 0;
-  if (!cur.next(c, g, TILE_KT, tl)) return;  // empty key range: the planner never produces one
-  cnt1 = tl.cnt;  // becomes tile 0 when step -1 hands over to step 0
-  pos1 = tl.pos;
-  refresh_offsets();
-  aim(0, 0);
-  issue_all();
-  if (cur.next(c, g, TILE_KT, tl)) {  // when the range ends the old tile stays in tl
-    cnt2 = tl.cnt;
-    pos2 = tl.pos;
-  }
-  if (offsets_stale()) refresh_offsets();
-  aim(1, 1);
-  issue_all();
-
-  wait_q<MB>(qf);
-  // From here on Q is only ever an AGPR operand: give it its home there, once, instead of a copy per use.
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[mb][ks]));
-
-  f32x16 sa[2][MB], sb[2][MB];
-  u32x4 pa[MB][4], pb[MB][4];
-  // Step 0 applies P(-1) = 0 to "V(-1)", stage 4 of the V ring: zero-fill it so that no stale NaN
-  // pattern meets those zeros.  (Every stage of the K ring is loaded before it is read.)
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) pb[mb][j] = u32x4{0, 0, 0, 0};
-  {
+  // Requests everything an item needs before its first step: Q (into registers), its first two K/V tiles
+  // (stages 0 and 1 of both rings) and a zero-filled "V(-1)" (stage 4 of the V ring: step 0 multiplies a
+  // zero P into it, so no stale NaN pattern may sit there).  Nothing is waited for.  Every stage of the
+  // rings must be free: no wavefront of the workgroup may still read or load into them.
+  auto begin_item = [&](const DkItem& item, const DkEntry& entry) __attribute__((always_inline)) {
+    it = item;
+    e = entry;
+    last_row = it.row0 + it.nrows - 1;
+    const int wave_row0 = it.row0 + wave * (MB * 32);
+    wave_active = wave_row0 <= last_row;
+    wave_min_limit = e.n + (min(wave_row0, last_row) >> c.gshift);
+    // keys at positions above this are invisible to every row of the wavefront: those tiles are skipped
+    wave_max_limit = wave_active ? e.n + (min(wave_row0 + MB * 32 - 1, last_row) >> c.gshift) : -1;
+    load_q<MB>(c, e, g, wave_row0, last_row, lane, qf, limit);
+    cur = KvCursor{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
+    cnt0 = pos0 = cnt2 = pos2 = 0;
+    (void)cur.next(c, g, TILE_KT, tl);  // the planner never produces an empty key range
+    cnt1 = tl.cnt;  // becomes tile 0 when step -1 hands over to step 0
+    pos1 = tl.pos;
+    refresh_offsets();
+    aim(0, 0);
+    issue_all();
+    if (cur.next(c, g, TILE_KT, tl)) {  // when the range ends the old tile stays in tl
+      cnt2 = tl.cnt;
+      pos2 = tl.pos;
+    }
+    if (offsets_stale()) refresh_offsets();
+    aim(1, 1);
+    issue_all();
     u32x4* z = (u32x4*)(v_ring + 4 * TILE_STAGE_BYTES);
 #pragma unroll
     for (int i = 0; i < TILE_STAGE_BYTES / (256 * 16); ++i) z[i * 256 + threadIdx.x] = u32x4{0, 0, 0, 0};
+  };
+
+  int trace_seq = 0;
+  (void)trace_seq;
+  DK_TR(0, 7);
+  int item_idx = load_desc(links, blockIdx.x / c.n_kv_heads);
+  {
+    const DkItem first = load_desc(c.items, item_idx);
+    begin_item(first, load_desc(c.entries, first.entry));
   }
 
-  bool mx_valid = false, pending = false;
-  float mx[MB] = {0.f, 0.f}, alpha[MB] = {1.f, 1.f};
-  float ms[MB] = {0.f, 0.f};  // the reference maxima as subtracted from the scores: m, or 0 while m = -inf
-  float gval = 0.f;           // how far the tile's scores outgrow the reference maxima (log2 units)
-
-  // step -1: S^T(0); requests tile 2
-  int cnt3 = 0, pos3 = 0;
-  auto fetch = [&]() {
-    cnt3 = 0;
-    if (cur.next(c, g, TILE_KT, tl)) {
-      cnt3 = tl.cnt;
-      pos3 = tl.pos;
+  while (true) {
+    // the next item of the chain: its descriptors arrive while this one is being computed
+    const int next_idx = load_desc(links, n_chains + item_idx);
+    DkItem next_item = it;
+    DkEntry next_entry = e;
+    if (next_idx >= 0) {
+      next_item = load_desc(c.items, next_idx);
+      next_entry = load_desc(c.entries, next_item.entry);
     }
-  };
-  fetch();
-  wait_vmcnt<8>();
-  __builtin_amdgcn_s_barrier();
-  if (offsets_stale()) refresh_offsets();
-  aim(2, 2);
-  issue_all();
-  if (wave_active) plain_s(k_ring, qf, sa, koff);
-  cnt0 = cnt1; pos0 = pos1;
-  cnt1 = cnt2; pos1 = pos2;
-  cnt2 = cnt3; pos2 = pos3;
-  fetch();
 
-  // byte offsets of the stages step t uses: K(t+1) read, K(t+3) written; V(t-1) read, V(t+3) written
-  int k_rd = 1 * TILE_STAGE_BYTES, k_wr = 0, v_rd = 4 * TILE_STAGE_BYTES, v_wr = 3 * TILE_STAGE_BYTES;
-#ifdef DK_PROF
-  long long pacc[6] = {0, 0, 0, 0, 0, 0};
-  const long long pstart = __builtin_readcyclecounter();
-  const long long wstart = wall_clock64();
-#endif
+    DK_TR(trace_seq, 0);
+    wait_q<MB>(qf);
+    DK_TR(trace_seq, 1);
+    // From here on Q is only ever an AGPR operand: give it its home there, once, instead of a copy per use.
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+a"(qf[mb][ks]));
 
-  // on to step t+1
-  auto advance = [&]() __attribute__((always_inline)) {
+    WaveState st;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      st.m[mb] = -INFINITY;
+      st.l[mb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        f32x16 z = {0};
+        asm volatile("" : "+a"(z));  // born in an AGPR tuple as a whole
+        st.o[db][mb] = z;
+      }
+    }
+
+    f32x16 sa[2][MB], sb[2][MB];
+    u32x4 pa[MB][4], pb[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pb[mb][j] = u32x4{0, 0, 0, 0};
+
+    bool mx_valid = false, pending = false;
+    float mx[MB] = {0.f, 0.f}, alpha[MB] = {1.f, 1.f};
+    float ms[MB] = {0.f, 0.f};  // the reference maxima as subtracted from the scores: m, or 0 while m = -inf
+    float gval = 0.f;           // how far the tile's scores outgrow the reference maxima (log2 units)
+
+    // step -1: S^T(0); requests tile 2
+    int cnt3 = 0, pos3 = 0;
+    auto fetch = [&]() {
+      cnt3 = 0;
+      if (cur.next(c, g, TILE_KT, tl)) {
+        cnt3 = tl.cnt;
+        pos3 = tl.pos;
+      }
+    };
+    fetch();
+    wait_vmcnt<8>();
+    __builtin_amdgcn_s_barrier();
+    if (offsets_stale()) refresh_offsets();
+    aim(2, 2);
+    issue_all();
+    if (wave_active) plain_s(k_ring, qf, sa, koff);
     cnt0 = cnt1; pos0 = pos1;
     cnt1 = cnt2; pos1 = pos2;
     cnt2 = cnt3; pos2 = pos3;
     fetch();
-    k_rd = k_rd == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_rd + TILE_STAGE_BYTES;
-    k_wr = k_wr == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_wr + TILE_STAGE_BYTES;
-    v_rd = v_rd == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_rd + TILE_STAGE_BYTES;
-    v_wr = v_wr == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_wr + TILE_STAGE_BYTES;
-  };
-  auto step = [&](f32x16(&sc)[2][MB], f32x16(&sn)[2][MB], u32x4(&pp)[MB][4], u32x4(&pc)[MB][4])
-                  __attribute__((always_inline)) {
-    wait_vmcnt<8>();
-    __builtin_amdgcn_s_barrier();
-    DK_PROF_T(t1);
-    const char* k_lds = k_ring + k_rd;
-    const char* v_lds = v_ring + v_rd;
-    ld.gk = tl.k;
-    ld.gv = tl.v;
-    ld.lds_k = k_ring_lds + k_wr;
-    ld.lds_v = v_ring_lds + v_wr;
-    if (!wave_active) {
-      // A wavefront whose rows lie past the end of a ragged row tile only does its share of the loads and
-      // keeps the barriers: no arithmetic, so it draws no matrix-pipe power either.
-      if (offsets_stale()) refresh_offsets();
-      issue_all();
-      advance();
-      return;
-    }
-    // a tile that does not exist or lies beyond the wavefront's rows counts as having no valid key
-    const int cnt_eff = pos0 <= wave_max_limit ? cnt0 : 0;
-    const bool need_mask = cnt_eff < TILE_KT || pos0 + TILE_KT - 1 > wave_min_limit;
-    if (pending || need_mask || !mx_valid || offsets_stale()) {  // rare, all of it
-      if (offsets_stale()) refresh_offsets();
-      if (pending) {  // O still carries the reference maxima of two steps ago
-        rescale_o(st, alpha);
-        pending = false;
-      }
-      if (need_mask) mask_tile(sc, limit, lane, cnt_eff, pos0);
-      if (need_mask || !mx_valid) {
-        row_max(sc, mx);
-        gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
-      }
-    }
-    if (__builtin_amdgcn_ballot_w64(gval > RESCALE_SLACK) != 0) {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const float mn = fmaxf(st.m[mb], mx[mb] * c.c);
-        const float mz = (mn == -INFINITY) ? 0.f : mn;
-        alpha[mb] = __builtin_amdgcn_exp2f(st.m[mb] - mz);  // 1 for rows whose maximum did not move
-        st.m[mb] = mn;
-        ms[mb] = mz;
-        st.l[mb] *= alpha[mb];
-      }
-      pending = true;
-    }
-    DK_PROF_T(t2);
-    {
-      FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, ms, c.c, koff, voff};
-      f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
-      f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
-      f.kf[1][0] = read_k_frag(k_lds, koff, 0, 1);
-      f.kf[1][1] = read_k_frag(k_lds, koff, 1, 1);
-      __builtin_amdgcn_sched_barrier(0);
-      f.scale<0>();
+
+    DK_TR(trace_seq, 2);
+    // byte offsets of the stages step t uses: K(t+1) read, K(t+3) written; V(t-1) read, V(t+3) written
+    int k_rd = 1 * TILE_STAGE_BYTES, k_wr = 0, v_rd = 4 * TILE_STAGE_BYTES, v_wr = 3 * TILE_STAGE_BYTES;
 #ifdef DK_PROF
-      f.run(std::make_integer_sequence<int, 32>{});
-      DK_PROF_T(tm);
-      DK_PROF_ADD(1, tm - t2);
-      f.run_from<32>(std::make_integer_sequence<int, 32>{});
+    long long pacc[6] = {0, 0, 0, 0, 0, 0};
+    const long long pstart = __builtin_readcyclecounter();
+    const long long wstart = wall_clock64();
+#endif
+
+    // on to step t+1
+    auto advance = [&]() __attribute__((always_inline)) {
+      cnt0 = cnt1; pos0 = pos1;
+      cnt1 = cnt2; pos1 = pos2;
+      cnt2 = cnt3; pos2 = pos3;
+      fetch();
+      k_rd = k_rd == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_rd + TILE_STAGE_BYTES;
+      k_wr = k_wr == (TILE_K_RING - 1) * TILE_STAGE_BYTES ? 0 : k_wr + TILE_STAGE_BYTES;
+      v_rd = v_rd == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_rd + TILE_STAGE_BYTES;
+      v_wr = v_wr == (TILE_V_RING - 1) * TILE_STAGE_BYTES ? 0 : v_wr + TILE_STAGE_BYTES;
+    };
+    auto step = [&](f32x16(&sc)[2][MB], f32x16(&sn)[2][MB], u32x4(&pp)[MB][4], u32x4(&pc)[MB][4])
+                    __attribute__((always_inline)) {
+      wait_vmcnt<8>();
+      __builtin_amdgcn_s_barrier();
+      DK_PROF_T(t1);
+      const char* k_lds = k_ring + k_rd;
+      const char* v_lds = v_ring + v_rd;
+      ld.gk = tl.k;
+      ld.gv = tl.v;
+      ld.lds_k = k_ring_lds + k_wr;
+      ld.lds_v = v_ring_lds + v_wr;
+      if (!wave_active) {
+        // A wavefront whose rows lie past the end of a ragged row tile only does its share of the loads and
+        // keeps the barriers: no arithmetic, so it draws no matrix-pipe power either.
+        if (offsets_stale()) refresh_offsets();
+        issue_all();
+        advance();
+        return;
+      }
+      // a tile that does not exist or lies beyond the wavefront's rows counts as having no valid key
+      const int cnt_eff = pos0 <= wave_max_limit ? cnt0 : 0;
+      const bool need_mask = cnt_eff < TILE_KT || pos0 + TILE_KT - 1 > wave_min_limit;
+      if (pending || need_mask || !mx_valid || offsets_stale()) {  // rare, all of it
+        if (offsets_stale()) refresh_offsets();
+        if (pending) {  // O still carries the reference maxima of two steps ago
+          rescale_o(st, alpha);
+          pending = false;
+        }
+        if (need_mask) mask_tile(sc, limit, lane, cnt_eff, pos0);
+        if (need_mask || !mx_valid) {
+          row_max(sc, mx);
+          gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
+        }
+      }
+      if (__builtin_amdgcn_ballot_w64(gval > RESCALE_SLACK) != 0) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const float mn = fmaxf(st.m[mb], mx[mb] * c.c);
+          const float mz = (mn == -INFINITY) ? 0.f : mn;
+          alpha[mb] = __builtin_amdgcn_exp2f(st.m[mb] - mz);  // 1 for rows whose maximum did not move
+          st.m[mb] = mn;
+          ms[mb] = mz;
+          st.l[mb] *= alpha[mb];
+        }
+        pending = true;
+      }
+      DK_PROF_T(t2);
+      {
+        FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, ms, c.c, koff, voff};
+        f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
+        f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
+        f.kf[1][0] = read_k_frag(k_lds, koff, 0, 1);
+        f.kf[1][1] = read_k_frag(k_lds, koff, 1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        f.scale<0>();
+#ifdef DK_PROF
+        f.run(std::make_integer_sequence<int, 32>{});
+        DK_PROF_T(tm);
+        DK_PROF_ADD(1, tm - t2);
+        f.run_from<32>(std::make_integer_sequence<int, 32>{});
 #else
-      f.run(std::make_integer_sequence<int, 64>{});
+        f.run(std::make_integer_sequence<int, 64>{});
 #endif
-      f.rowsum<63>();
-      f.pack<31>();
+        f.rowsum<63>();
+        f.pack<31>();
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) mx[mb] = f.mxn[mb];
-      // -inf - -inf for rows that have seen no key yet: NaN compares false, which is right (nothing to raise)
-      gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
-      mx_valid = true;
-    }
-    DK_PROF_T(t3);
-    DK_PROF_ADD(2, t3 - t1);
-    DK_PROF_ADD(3, 1);
-    advance();
-  };
+        for (int mb = 0; mb < MB; ++mb) mx[mb] = f.mxn[mb];
+        // -inf - -inf for rows that have seen no key yet: NaN compares false, which is right (nothing to raise)
+        gval = fmaxf(__builtin_fmaf(mx[0], c.c, -st.m[0]), __builtin_fmaf(mx[1], c.c, -st.m[1]));
+        mx_valid = true;
+      }
+      DK_PROF_T(t3);
+      DK_PROF_ADD(2, t3 - t1);
+      DK_PROF_ADD(3, 1);
+      advance();
+    };
 
-  // steps 0 .. T for T tiles: the last one only applies P(T-1)
-  while (true) {
-    bool last = cnt0 == 0;
-    step(sa, sb, pb, pa);
-    if (last) break;
-    last = cnt0 == 0;
-    step(sb, sa, pa, pb);
-    if (last) break;
-  }
-  if (pending) rescale_o(st, alpha);
-  wait_vmcnt<0>();
+    // steps 0 .. T for T tiles: the last one only applies P(T-1)
+    while (true) {
+      bool last = cnt0 == 0;
+      step(sa, sb, pb, pa);
+      if (last) break;
+      last = cnt0 == 0;
+      step(sb, sa, pa, pb);
+      if (last) break;
+    }
+    if (pending) rescale_o(st, alpha);
+    wait_vmcnt<0>();
+    DK_TR(trace_seq, 3);
 
 #ifdef DK_PROF
-  if (lane == 0) {
-    atomicAdd(&g_prof[0], (unsigned long long)(__builtin_readcyclecounter() - pstart));
-    atomicAdd(&g_prof[2], (unsigned long long)pacc[1]);
-    atomicAdd(&g_prof[3], (unsigned long long)pacc[2]);
-    atomicAdd(&g_prof[4], (unsigned long long)pacc[3]);
-    atomicAdd(&g_prof[6], (unsigned long long)(wall_clock64() - wstart));
-  }
+    if (lane == 0) {
+      atomicAdd(&g_prof[0], (unsigned long long)(__builtin_readcyclecounter() - pstart));
+      atomicAdd(&g_prof[2], (unsigned long long)pacc[1]);
+      atomicAdd(&g_prof[3], (unsigned long long)pacc[2]);
+      atomicAdd(&g_prof[4], (unsigned long long)pacc[3]);
+      atomicAdd(&g_prof[6], (unsigned long long)(wall_clock64() - wstart));
+    }
 #endif
-  if (wave_active) {
+    // what the store below needs of the finished item
+    const DkItem done_item = it;
+    const DkEntry done_entry = e;
+    const bool done_active = wave_active;
+    if (next_idx >= 0) {
+      // every wavefront has left the last step: the rings are free for the next item's first loads, which
+      // then travel while this item's output is being stored
+      __builtin_amdgcn_s_barrier();
+      begin_item(next_item, next_entry);
+    }
+    DK_TR(trace_seq, 4);
+    if (done_active) {
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) settle_acc(st.o[db][mb]);
-    float ltot[MB];
+        for (int mb = 0; mb < MB; ++mb) settle_acc(st.o[db][mb]);
+      float ltot[MB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) ltot[mb] = st.l[mb] + __shfl_xor(st.l[mb], 32);
+      for (int mb = 0; mb < MB; ++mb) ltot[mb] = st.l[mb] + __shfl_xor(st.l[mb], 32);
 #pragma unroll
-    for (int db = 0; db < 4; ++db) store_block<MB>(c, e, it, g, wave * (MB * 32), lane, db, st.o[db], ltot);
-    store_ml<MB>(c, e, it, g, wave * (MB * 32), lane, st.m, ltot);
+      for (int db = 0; db < 4; ++db)
+        store_block<MB>(c, done_entry, done_item, g, wave * (MB * 32), lane, db, st.o[db], ltot);
+      store_ml<MB>(c, done_entry, done_item, g, wave * (MB * 32), lane, st.m, ltot);
+    }
+    DK_TR(trace_seq, 5);
+#ifdef DK_TRACE
+    if (threadIdx.x == 0 && trace_seq < 16 && blockIdx.x < 256)
+      g_trace[blockIdx.x][trace_seq][6] = (unsigned long long)((done_item.kv_hi - done_item.kv_lo + 63) / 64);
+    ++trace_seq;
+#endif
+    if (next_idx < 0) break;
+    item_idx = next_idx;
   }
 }
 
 }  // namespace mfma
 
-hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream) {
+hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
+                              hipStream_t stream) {
   using namespace mfma;
-  if (n_items <= 0) return hipSuccess;
+  if (n_chains <= 0) return hipSuccess;
   if (a.arena.head_dim != D || a.arena.dtype != 1) return hipErrorInvalidValue;
   // once per process, whatever thread or pool gets here first
   static std::once_flag attr_once;
@@ -642,7 +712,8 @@ hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t 
   });
   if (attr_status != hipSuccess) return attr_status;
   const Ctx c = make_ctx(a, items);
-  attend_tile_kernel<<<dim3((unsigned)n_items * a.arena.n_kv_heads), 256, TILE_LDS_BYTES, stream>>>(c);
+  attend_tile_kernel<<<dim3((unsigned)n_chains * a.arena.n_kv_heads), 256, TILE_LDS_BYTES, stream>>>(c, links,
+                                                                                                      n_chains);
   return hipGetLastError();
 }
 

@@ -46,7 +46,10 @@ struct AttendArgs {
 // Scalar reference kernel: one wavefront per (token, query head).  Any supported shape and dtype.
 hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream);
 // bf16 MFMA kernels (head_dim 128).
-hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, int32_t n_items, hipStream_t stream);
+// One workgroup per (chain, KV head): chain c is items links[c], links[n_chains + that item], ... until a link
+// is negative; every chain holds at least one item.
+hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
+                              hipStream_t stream);
 // Unit u = item u / n_kv_heads for KV head u % n_kv_heads.  Workgroup w walks the chain links[w],
 // links[n_chains + that unit], ... until a link is negative.
 // max_rows: the largest DkItem::nrows among the items (at most 64).

@@ -18,7 +18,7 @@ typedef PlanKeyedItem Keyed;
 // read the same K/V tiles, so they are made neighbours in launch order (`group` = true) and, running
 // at the same time on the XCD of their KV head, fetch each tile from HBM once and from L2 after that.
 void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk, bool group,
-               int32_t wave_slots, std::vector<Keyed>& keyed, std::vector<int64_t>& cost, std::vector<DkItem>* items,
+               int32_t wave_slots, int32_t item_cost, std::vector<Keyed>& keyed, std::vector<int64_t>& cost, std::vector<DkItem>* items,
                std::vector<DkMerge>* merges, int64_t* part_rows) {
   if (tiles.empty()) return;
   int64_t total = 0;
@@ -32,10 +32,10 @@ void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t targe
   if (group && wave_slots > 0) {
     // Tile kernel: pick the chunk length by a small cost model instead.  `wave_slots` workgroups of a KV
     // head run at a time, so n items take ceil(n / wave_slots) rounds; a round lasts as long as an item,
-    // (work / n) key tiles plus the fixed cost of a workgroup (descriptor and Q loads, pipeline ramp,
-    // output store: about 12 us, or seven key tiles).  Splitting finer shortens the rounds but adds
-    // rounds and fixed costs; what matters most is landing on a whole number of rounds.
-    const double fixed = 7.0;
+    // (work / n) key tiles plus the fixed cost of an item (pipeline ramp, output store; `item_cost` key
+    // tiles).  Splitting finer shortens the rounds but adds rounds, fixed costs and partial rows to merge;
+    // what matters most is landing on a whole number of rounds.
+    const double fixed = (double)item_cost;
     const double work = (double)total / kv_tile;
     double best = 0;
     int64_t best_chunk = 0;
@@ -159,6 +159,36 @@ void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::v
     std::push_heap(heap.begin(), heap.end(), later);
   }
 }
+// The tile kernel runs `slots` workgroups per KV head, each walking a chain of items.  The items arrive in launch
+// order (grouped by (entry, key chunk), costliest group first) and each joins the chain that is free first, which is
+// what a hardware dispatcher would do with one workgroup per item -- so the row tiles of a group still run at the
+// same time and share their K/V tiles through L2 -- but without a workgroup start per item.
+void chain_tile_items(const std::vector<DkItem>& items, int32_t kv_tile, int32_t slots, int32_t item_cost,
+                      std::vector<std::pair<double, int32_t>>& heap, std::vector<int32_t>& tail,
+                      std::vector<int32_t>* links, int32_t* n_chains) {
+  const int32_t n = (int32_t)items.size();
+  const int32_t chains = std::min(n, std::max(slots, 1));
+  *n_chains = chains;
+  links->assign((size_t)chains + (size_t)n, -1);
+  if (n == 0) return;
+  int32_t* head = links->data();
+  int32_t* next = links->data() + chains;
+  typedef std::pair<double, int32_t> Free;  // (time at which the chain is free, chain)
+  heap.resize((size_t)chains);
+  for (int32_t c = 0; c < chains; ++c) heap[c] = {0.0, c};
+  const auto later = [](const Free& a, const Free& b) { return a > b; };
+  std::make_heap(heap.begin(), heap.end(), later);
+  tail.assign((size_t)chains, -1);
+  for (int32_t i = 0; i < n; ++i) {
+    std::pop_heap(heap.begin(), heap.end(), later);
+    Free& f = heap.back();
+    const int32_t c = f.second;
+    if (tail[c] < 0) head[c] = i; else next[tail[c]] = i;
+    tail[c] = i;
+    f.first += (double)((items[i].kv_hi - items[i].kv_lo + kv_tile - 1) / kv_tile + item_cost);
+    std::push_heap(heap.begin(), heap.end(), later);
+  }
+}
 }  // namespace
 
 int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
@@ -172,6 +202,8 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
   p->merges.clear();
   p->stream_links.clear();
   p->stream_chains = 0;
+  p->tile_links.clear();
+  p->tile_chains = 0;
   p->part_rows = 0;
   p->total_tokens = n_seqs ? cu_delta[n_seqs] : 0;
   const int32_t group = cfg.n_q_heads / cfg.n_kv_heads;
@@ -211,10 +243,12 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
       }
     }
   }
-  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, p->keyed, p->cost,
+  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, cfg.tile_item_cost, p->keyed, p->cost,
             &p->tile_items, &p->merges, &p->part_rows);
-  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, p->keyed, p->cost,
+  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, 0, p->keyed, p->cost,
             &p->stream_items, &p->merges, &p->part_rows);
+  chain_tile_items(p->tile_items, cfg.kv_tile, cfg.tile_wave_slots, cfg.tile_item_cost, p->heap, p->tail,
+                   &p->tile_links, &p->tile_chains);
   chain_units(p->stream_items, cfg, p->heap, p->tail, &p->stream_links, &p->stream_chains);
 
   size_t off = 0;
@@ -224,6 +258,8 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
   off = align_up(off + p->segs.size() * sizeof(DkSeg), 256);
   p->off_tile = off;
   off = align_up(off + p->tile_items.size() * sizeof(DkItem), 256);
+  p->off_tile_links = off;
+  off = align_up(off + p->tile_links.size() * sizeof(int32_t), 256);
   p->off_stream = off;
   off = align_up(off + p->stream_items.size() * sizeof(DkItem), 256);
   p->off_links = off;

@@ -22,6 +22,7 @@ struct PlanConfig {
   int32_t tile_wave_slots;  // tile-kernel workgroups of one KV head that run at a time (its share of the CUs)
   int32_t stream_target;  // same, streaming kernel
   int32_t tile_min_chunk, stream_min_chunk;  // smallest key range worth its own item
+  int32_t tile_item_cost;    // fixed cost of a tile item inside a chain, in key tiles (store phase, pipeline ramp)
   int32_t stream_chains;     // workgroups of the streaming kernel: one per compute unit
   int32_t stream_item_cost;  // fixed cost of an item in the chain balance, in keys
   float xcd_speed[8];        // relative K/V streaming rate of the XCD that workgroup w lands on (w % 8)
@@ -58,7 +59,11 @@ struct AttendPlan {
   // chain stream_links[w], stream_links[n_chains + that unit], ... until a link is negative.
   std::vector<int32_t> stream_links;
   int32_t stream_chains = 0;
-  size_t off_entries = 0, off_segs = 0, off_tile = 0, off_stream = 0, off_links = 0, off_merges = 0;
+  // Tile kernel: tile_wave_slots workgroups per KV head, workgroup c of a head walks the items
+  // tile_links[c], tile_links[tile_chains + that item], ...; the chains are the same for every KV head.
+  std::vector<int32_t> tile_links;
+  int32_t tile_chains = 0;
+  size_t off_entries = 0, off_segs = 0, off_tile = 0, off_tile_links = 0, off_stream = 0, off_links = 0, off_merges = 0;
   size_t blob_bytes = 0;   // descriptors
   size_t off_parts = 0;    // fp32 partial rows, each (head_dim + 2) floats per KV head
   size_t total_bytes = 0;  // whole workspace

@@ -33,6 +33,7 @@ static dk::PlanConfig config(int hq, int hkv) {
   c.tile_wave_slots = 256 / hkv;
   c.stream_target = 256 / hkv;
   c.tile_min_chunk = 128;
+  c.tile_item_cost = 3;
   c.stream_min_chunk = 512;
   c.stream_chains = 256;
   c.stream_item_cost = 512;
@@ -104,6 +105,33 @@ static void run_case(const Case& cs, int hq, int hkv, const float* speeds, doubl
         CHECK(kv.second.back().second == cs.n[b] + last_tok + 1);
       }
     CHECK(covered == rows);
+  }
+  // chains of the tile kernel: every item in exactly one chain, no empty chain, at most tile_wave_slots of them
+  {
+    const int32_t n_items = (int32_t)p.tile_items.size();
+    CHECK(p.tile_chains == std::min(n_items, cfg.tile_wave_slots));
+    CHECK((int64_t)p.tile_links.size() == (int64_t)p.tile_chains + n_items);
+    std::vector<int> hit((size_t)n_items, 0);
+    std::vector<double> busy((size_t)p.tile_chains, 0.0);
+    double sum = 0, longest_item = 0;
+    for (int32_t c = 0; c < p.tile_chains; ++c) {
+      int32_t steps = 0;
+      CHECK(p.tile_links[c] >= 0);
+      for (int32_t i = p.tile_links[c]; i >= 0 && steps <= n_items; i = p.tile_links[p.tile_chains + i], ++steps) {
+        CHECK(i < n_items);
+        if (i >= n_items) break;
+        ++hit[i];
+        const double cost = (p.tile_items[i].kv_hi - p.tile_items[i].kv_lo + 63) / 64 + cfg.tile_item_cost;
+        busy[c] += cost;
+        sum += cost;
+        longest_item = std::max(longest_item, cost);
+      }
+      CHECK(steps <= n_items);  // no cycle
+    }
+    for (int32_t i = 0; i < n_items; ++i) CHECK(hit[i] == 1);
+    // list scheduling: no chain ends later than the average plus one item
+    if (p.tile_chains > 0)
+      CHECK(*std::max_element(busy.begin(), busy.end()) <= sum / p.tile_chains + longest_item + 1e-9);
   }
   // chains of the streaming kernel
   const int64_t n_units = (int64_t)p.stream_items.size() * hkv;
