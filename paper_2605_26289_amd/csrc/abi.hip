@@ -189,13 +189,12 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
     c.tile_rows = 256;
     c.stream_rows = 64;
     c.kv_tile = 64;
-    c.tile_target = 3 * 256 / desc->n_kv_heads;
     // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
     // item costs a ramp-up, a partial write and merge work, and the planner's chains balance the rest
     c.stream_target = std::max(1, 256 / desc->n_kv_heads);
     c.tile_wave_slots = std::max(1, 256 / desc->n_kv_heads);
     c.tile_min_chunk = 128;
-    c.tile_item_cost = 3;
+    c.tile_item_cost = 5;
     c.stream_min_chunk = 512;
     c.stream_chains = 256;
     c.stream_item_cost = 512;
@@ -415,6 +414,7 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   a.out = out;
   a.lse = lse;
   a.parts = (float*)(ws + plan.off_parts);
+  a.parts_ml = a.parts + (size_t)plan.part_rows * pool->desc.n_kv_heads * pool->desc.head_dim;
   a.scale = scale;
   a.total_tokens = (int32_t)plan.total_tokens;
 

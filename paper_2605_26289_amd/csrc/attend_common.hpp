@@ -18,7 +18,8 @@ typedef __attribute__((address_space(1))) const void* glb_void_ptr;
 
 constexpr int D = 128;
 constexpr int ROW_BYTES = 256;
-constexpr int PS = D + 2;  // floats per partial row: D sums, running max (log2 units), weight sum
+// Split partials: per (partial row, KV head) D unnormalised fp32 sums in `parts` (512-byte rows) and the pair
+// (running maximum in log2 units, weight sum) in `parts_ml`.
 
 // Descriptors are read through the constant address space so that uniform reads become scalar loads
 // (they must not take part in the vector-memory counter that tracks the K/V tiles in flight).
@@ -46,6 +47,7 @@ struct Ctx {
   __bf16* __restrict__ out;
   float* __restrict__ lse;
   float* __restrict__ parts;
+  float* __restrict__ parts_ml;
   float c;  // softmax scale * log2(e): scores are handled in log2 units
   int32_t n_q_heads, n_kv_heads, gshift;
   int64_t arena_cells;
@@ -198,13 +200,10 @@ __device__ __forceinline__ void store_block(const Ctx& c, const DkEntry& e, cons
     const int rl = row_local0 + mb * 32 + (lane & 31);
     if (rl >= it.nrows) continue;
     if (it.part_row0 >= 0) {
-      float* p = c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * PS + db * 32 + 4 * h;
+      float* p = c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * D + db * 32 + 4 * h;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        // PS is even, so every row starts 8-byte aligned: two float2 stores
-        *(float2*)(p + 8 * r4) = make_float2(o[mb][4 * r4], o[mb][4 * r4 + 1]);
-        *(float2*)(p + 8 * r4 + 2) = make_float2(o[mb][4 * r4 + 2], o[mb][4 * r4 + 3]);
-      }
+      for (int r4 = 0; r4 < 4; ++r4)
+        *(f32x4*)(p + 8 * r4) = f32x4{o[mb][4 * r4], o[mb][4 * r4 + 1], o[mb][4 * r4 + 2], o[mb][4 * r4 + 3]};
     } else {
       const int row = it.row0 + rl;
       const int tok = e.tok0 + (row >> c.gshift);
@@ -222,6 +221,80 @@ __device__ __forceinline__ void store_block(const Ctx& c, const DkEntry& e, cons
   }
 }
 
+// The same store through a private LDS staging area of 8 KiB, so that every store instruction of the wavefront
+// writes eight whole 128-byte pieces of eight rows instead of 64 scattered 8-byte pieces: the accumulator
+// layout (lane = row) is turned into (8 lanes = 128 bytes of one row) on the way.  16-byte chunks of a staged
+// row are XOR-swizzled with the row number, which keeps both the writes (one row per lane) and the reads
+// (eight lanes per row) free of bank conflicts.  Covers 64 rows x all 128 depths: four passes of one depth
+// block for fp32 partials, two passes of two depth blocks for the bf16 output.  LDS operations of one
+// wavefront execute in order, so no wait is needed between a pass's writes and reads or between passes.
+template <int MB>
+__device__ __forceinline__ void store_rows_staged(const Ctx& c, const DkEntry& e, const DkItem& it, int g,
+                                                  int row_local0, int lane, char* stage, const f32x16 (&o)[4][MB],
+                                                  const float (&ltot)[MB]) {
+  static_assert(MB == 2, "64 rows per wavefront");
+  const int h = lane >> 5, r = lane & 31;
+  const int rd_row = lane >> 3, rd_chunk = lane & 7;  // reader: row inside a group of eight, 16-byte chunk
+  const int gmask = (1 << c.gshift) - 1;
+  if (it.part_row0 >= 0) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int R = mb * 32 + r;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *(f32x4*)(stage + R * 128 + (((2 * r4 + h) ^ (R & 7)) << 4)) =
+              f32x4{o[db][mb][4 * r4], o[db][mb][4 * r4 + 1], o[db][mb][4 * r4 + 2], o[db][mb][4 * r4 + 3]};
+      }
+#pragma unroll
+      for (int ps = 0; ps < 8; ++ps) {
+        const int R = ps * 8 + rd_row;
+        const f32x4 v = *(const f32x4*)(stage + R * 128 + ((rd_chunk ^ (R & 7)) << 4));
+        const int rl = row_local0 + R;
+        if (rl < it.nrows)
+          *(f32x4*)(c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * D + db * 32 + rd_chunk * 4) = v;
+      }
+      __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps the passes' registers from piling up
+    }
+  } else {
+    float inv[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) inv[mb] = 1.f / ltot[mb];
+#pragma unroll
+    for (int dp = 0; dp < 2; ++dp) {  // depth blocks 2 dp and 2 dp + 1: 64 bf16 = 128 bytes per row
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int R = mb * 32 + r;
+#pragma unroll
+        for (int d2 = 0; d2 < 2; ++d2)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            bf16x4 v;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = (__bf16)(o[2 * dp + d2][mb][4 * r4 + t] * inv[mb]);
+            // bf16 columns d2*32 + 8*r4 + 4h .. +3: 8-byte piece (8*d2 + 2*r4 + h) of the 128-byte row
+            const int piece = 8 * d2 + 2 * r4 + h;
+            *(bf16x4*)(stage + R * 128 + ((((piece >> 1) ^ (R & 7)) << 4) | ((piece & 1) << 3))) = v;
+          }
+      }
+#pragma unroll
+      for (int ps = 0; ps < 8; ++ps) {
+        const int R = ps * 8 + rd_row;
+        const bf16x8 v = *(const bf16x8*)(stage + R * 128 + ((rd_chunk ^ (R & 7)) << 4));
+        const int rl = row_local0 + R;
+        if (rl < it.nrows) {
+          const int row = it.row0 + rl;
+          const int tok = e.tok0 + (row >> c.gshift);
+          const int head = (g << c.gshift) + (row & gmask);
+          *(bf16x8*)(c.out + ((int64_t)tok * c.n_q_heads + head) * D + dp * 64 + rd_chunk * 8) = v;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
 // Running maximum and weight sum of each row (partials) or the row's log-sum-exp (final output).
 template <int MB>
 __device__ __forceinline__ void store_ml(const Ctx& c, const DkEntry& e, const DkItem& it, int g, int row_local0,
@@ -233,9 +306,8 @@ __device__ __forceinline__ void store_ml(const Ctx& c, const DkEntry& e, const D
     const int rl = row_local0 + mb * 32 + lane;
     if (rl >= it.nrows) continue;
     if (it.part_row0 >= 0) {
-      float* p = c.parts + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * PS;
-      p[D] = m[mb];
-      p[D + 1] = ltot[mb];
+      float* p = c.parts_ml + ((int64_t)(it.part_row0 + rl) * c.n_kv_heads + g) * 2;
+      *(float2*)p = make_float2(m[mb], ltot[mb]);
     } else if (c.lse) {
       const int row = it.row0 + rl;
       const int tok = e.tok0 + (row >> c.gshift);
@@ -263,6 +335,7 @@ inline Ctx make_ctx(const AttendArgs& a, const DkItem* items) {
   c.out = (__bf16*)a.out;
   c.lse = a.lse;
   c.parts = a.parts;
+  c.parts_ml = a.parts_ml;
   c.c = a.scale * 1.4426950408889634f;
   c.n_q_heads = a.arena.n_q_heads;
   c.n_kv_heads = a.arena.n_kv_heads;

@@ -665,12 +665,11 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
     const DkItem done_item = it;
     const DkEntry done_entry = e;
     const bool done_active = wave_active;
-    if (next_idx >= 0) {
-      // every wavefront has left the last step: the rings are free for the next item's first loads, which
-      // then travel while this item's output is being stored
-      __builtin_amdgcn_s_barrier();
-      begin_item(next_item, next_entry);
-    }
+    // Every wavefront has left the last step: the rings are free.  The next item's first loads are requested
+    // now and travel while this item's output is being stored; the store is staged through the part of the V
+    // ring those loads do not touch (stages 2 and 3, 8 KiB per wavefront).
+    __builtin_amdgcn_s_barrier();
+    if (next_idx >= 0) begin_item(next_item, next_entry);
     DK_TR(trace_seq, 4);
     if (done_active) {
 #pragma unroll
@@ -680,10 +679,13 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
       float ltot[MB];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) ltot[mb] = st.l[mb] + __shfl_xor(st.l[mb], 32);
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-        store_block<MB>(c, done_entry, done_item, g, wave * (MB * 32), lane, db, st.o[db], ltot);
-      store_ml<MB>(c, done_entry, done_item, g, wave * (MB * 32), lane, st.m, ltot);
+      // (the lane number is laundered so that the store phase's per-lane offsets are computed here, each time,
+      // instead of being hoisted out of the item loop, where they would sit in registers the key loop needs)
+      int store_lane = lane;
+      asm volatile("" : "+v"(store_lane));
+      store_rows_staged<MB>(c, done_entry, done_item, g, wave * (MB * 32), store_lane,
+                            v_ring + 2 * TILE_STAGE_BYTES + wave * 8192, st.o, ltot);
+      store_ml<MB>(c, done_entry, done_item, g, wave * (MB * 32), store_lane, st.m, ltot);
     }
     DK_TR(trace_seq, 5);
 #ifdef DK_TRACE

@@ -38,7 +38,8 @@ struct AttendArgs {
   const void* v_new;
   void* out;
   float* lse;
-  float* parts;
+  float* parts;     // split partials: [partial row][KV head][head_dim] fp32 sums
+  float* parts_ml;  // [partial row][KV head][2]: running maximum (log2 units), weight sum
   float scale;
   int32_t total_tokens;
 };

@@ -247,85 +247,126 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Merge of split key ranges.  Each split left, per (row, KV head), D unnormalised fp32 sums, its
-// running maximum m (log2 units) and its weight sum l.  O = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
-// One wavefront per (row, KV head): first every lane takes one split and fetches its (m, l), which gives
-// the common maximum, the weights and the weight sum in one round trip; then the lanes cover D and add
-// the splits' sums, four independent loads in flight at a time.
+// Merge of split key ranges.  Each split left, per (row, KV head), D unnormalised fp32 sums (parts) and its
+// running maximum m (log2 units) with its weight sum l (parts_ml).
+//   O = sum_s 2^(m_s-M) o_s / sum_s 2^(m_s-M) l_s.
+// A wavefront merges MERGE_ROWS rows of one KV head at a time: for each row every lane first takes one split
+// and fetches its (m, l), which gives the common maximum, the weights and the weight sum in one round trip;
+// then the lanes cover D and add the splits' sums, the loads of all the rows and of two splits in flight
+// together.  (One row per wavefront left most of a launch's time to workgroup turnover when rows are split
+// only two or three ways.)
 // ---------------------------------------------------------------------------------------------
+constexpr int MERGE_ROWS = 4;  // rows per wavefront; a workgroup of four wavefronts covers 16 rows
+
 template <int D>
 __global__ __launch_bounds__(256) void attend_merge_kernel(const DkMerge* __restrict__ merges,
                                                            const DkEntry* __restrict__ entries,
-                                                           const float* __restrict__ parts, __bf16* __restrict__ out,
+                                                           const float* __restrict__ parts,
+                                                           const float* __restrict__ parts_ml, __bf16* __restrict__ out,
                                                            float* __restrict__ lse, int32_t n_q_heads,
                                                            int32_t n_kv_heads) {
-  constexpr int PS = D + 2;
   static_assert(D == 128, "two floats per lane");
   const DkMerge mg = merges[blockIdx.x];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int r = blockIdx.z * 4 + wave;
-  if (r >= mg.nrows) return;
+  const int r0 = (blockIdx.z * 4 + wave) * MERGE_ROWS;
+  if (r0 >= mg.nrows) return;
   const DkEntry e = entries[mg.entry];
   const int g = blockIdx.y;
   const int group = n_q_heads / n_kv_heads;
-  const float* p0 = parts + ((int64_t)(mg.part_row0 + r) * n_kv_heads + g) * PS;
-  const int64_t stride = (int64_t)mg.nrows * n_kv_heads * PS;  // from one split of the row to the next
+  const int64_t srow = (int64_t)mg.nrows * n_kv_heads;  // partial rows from one split of a row to the next
+  const int64_t stride = srow * D;
 
-  float mmax = -INFINITY;
-  for (int s = lane; s < mg.nsplit; s += 64) mmax = fmaxf(mmax, p0[s * stride + D]);
+  const float* p0[MERGE_ROWS];
+  const float* ml0[MERGE_ROWS];
+  bool live[MERGE_ROWS];
 #pragma unroll
-  for (int off = 32; off; off >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, off));
+  for (int i = 0; i < MERGE_ROWS; ++i) {
+    live[i] = r0 + i < mg.nrows;
+    const int64_t prow = (int64_t)(mg.part_row0 + (live[i] ? r0 + i : r0)) * n_kv_heads + g;
+    p0[i] = parts + prow * D + lane * 2;
+    ml0[i] = parts_ml + prow * 2;
+  }
 
-  float2 acc = {0.f, 0.f};
-  float lsum = 0.f;
+  float2 acc[MERGE_ROWS];
+  float lsum[MERGE_ROWS], mmax[MERGE_ROWS];
+#pragma unroll
+  for (int i = 0; i < MERGE_ROWS; ++i) {
+    acc[i] = make_float2(0.f, 0.f);
+    lsum[i] = 0.f;
+    float m = -INFINITY;
+    for (int s = lane; s < mg.nsplit; s += 64) m = fmaxf(m, ml0[i][s * srow * 2]);
+    mmax[i] = m;
+  }
+#pragma unroll
+  for (int off = 32; off; off >>= 1)
+#pragma unroll
+    for (int i = 0; i < MERGE_ROWS; ++i) mmax[i] = fmaxf(mmax[i], __shfl_xor(mmax[i], off));
+
   for (int s0 = 0; s0 < mg.nsplit; s0 += 64) {
     const int mine = s0 + lane;
-    float w_mine = 0.f;
-    if (mine < mg.nsplit) {
-      const float ms = p0[mine * stride + D];  // second touch: served from cache
-      w_mine = (ms == -INFINITY) ? 0.f : exp2f(ms - mmax);
-      lsum += w_mine * p0[mine * stride + D + 1];
+    float w_mine[MERGE_ROWS];
+#pragma unroll
+    for (int i = 0; i < MERGE_ROWS; ++i) {
+      w_mine[i] = 0.f;
+      if (mine < mg.nsplit) {
+        const float2 ml = *(const float2*)(ml0[i] + mine * srow * 2);  // second touch: served from cache
+        w_mine[i] = (ml.x == -INFINITY) ? 0.f : exp2f(ml.x - mmax[i]);
+        lsum[i] += w_mine[i] * ml.y;
+      }
     }
     const int cnt = min(64, mg.nsplit - s0);
-    const float* p = p0 + s0 * stride + lane * 2;
     int s = 0;
-    for (; s + 4 <= cnt; s += 4) {
-      const float2 v0 = *(const float2*)(p + (s + 0) * stride);
-      const float2 v1 = *(const float2*)(p + (s + 1) * stride);
-      const float2 v2 = *(const float2*)(p + (s + 2) * stride);
-      const float2 v3 = *(const float2*)(p + (s + 3) * stride);
-      const float w0 = __shfl(w_mine, s + 0), w1 = __shfl(w_mine, s + 1);
-      const float w2 = __shfl(w_mine, s + 2), w3 = __shfl(w_mine, s + 3);
-      acc.x += w0 * v0.x + w1 * v1.x + w2 * v2.x + w3 * v3.x;
-      acc.y += w0 * v0.y + w1 * v1.y + w2 * v2.y + w3 * v3.y;
+    for (; s + 2 <= cnt; s += 2) {
+      float2 v0[MERGE_ROWS], v1[MERGE_ROWS];
+#pragma unroll
+      for (int i = 0; i < MERGE_ROWS; ++i) {
+        v0[i] = *(const float2*)(p0[i] + (s0 + s) * stride);
+        v1[i] = *(const float2*)(p0[i] + (s0 + s + 1) * stride);
+      }
+#pragma unroll
+      for (int i = 0; i < MERGE_ROWS; ++i) {
+        const float w0 = __shfl(w_mine[i], s), w1 = __shfl(w_mine[i], s + 1);
+        acc[i].x += w0 * v0[i].x + w1 * v1[i].x;
+        acc[i].y += w0 * v0[i].y + w1 * v1[i].y;
+      }
     }
-    for (; s < cnt; ++s) {
-      const float2 v = *(const float2*)(p + s * stride);
-      const float w = __shfl(w_mine, s);
-      acc.x += w * v.x;
-      acc.y += w * v.y;
+    if (s < cnt) {
+#pragma unroll
+      for (int i = 0; i < MERGE_ROWS; ++i) {
+        const float2 v = *(const float2*)(p0[i] + (s0 + s) * stride);
+        const float w = __shfl(w_mine[i], s);
+        acc[i].x += w * v.x;
+        acc[i].y += w * v.y;
+      }
     }
   }
 #pragma unroll
-  for (int off = 32; off; off >>= 1) lsum += __shfl_xor(lsum, off);
+  for (int off = 32; off; off >>= 1)
+#pragma unroll
+    for (int i = 0; i < MERGE_ROWS; ++i) lsum[i] += __shfl_xor(lsum[i], off);
 
-  const int row = mg.row0 + r;
-  const int tok = e.tok0 + row / group;
-  const int h = g * group + row % group;
-  const float inv = 1.f / lsum;
-  __bf16* o = out + ((int64_t)tok * n_q_heads + h) * D + lane * 2;
-  o[0] = (__bf16)(acc.x * inv);
-  o[1] = (__bf16)(acc.y * inv);
-  if (lse && lane == 0) lse[(int64_t)tok * n_q_heads + h] = (mmax + log2f(lsum)) * 0.6931471805599453f;
+#pragma unroll
+  for (int i = 0; i < MERGE_ROWS; ++i) {
+    if (!live[i]) continue;
+    const int row = mg.row0 + r0 + i;
+    const int tok = e.tok0 + row / group;
+    const int h = g * group + row % group;
+    const float inv = 1.f / lsum[i];
+    __bf16* o = out + ((int64_t)tok * n_q_heads + h) * D + lane * 2;
+    o[0] = (__bf16)(acc[i].x * inv);
+    o[1] = (__bf16)(acc[i].y * inv);
+    if (lse && lane == 0) lse[(int64_t)tok * n_q_heads + h] = (mmax[i] + log2f(lsum[i])) * 0.6931471805599453f;
+  }
 }
 
 hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, int32_t max_rows,
                                hipStream_t stream) {
   if (n_merges <= 0) return hipSuccess;
   if (a.arena.head_dim != 128 || max_rows <= 0) return hipErrorInvalidValue;
-  dim3 grid((unsigned)n_merges, (unsigned)a.arena.n_kv_heads, (unsigned)((max_rows + 3) / 4));
-  attend_merge_kernel<128><<<grid, 256, 0, stream>>>(merges, a.entries, a.parts, (__bf16*)a.out, a.lse,
+  const int rows_per_block = 4 * MERGE_ROWS;
+  dim3 grid((unsigned)n_merges, (unsigned)a.arena.n_kv_heads, (unsigned)((max_rows + rows_per_block - 1) / rows_per_block));
+  attend_merge_kernel<128><<<grid, 256, 0, stream>>>(merges, a.entries, a.parts, a.parts_ml, (__bf16*)a.out, a.lse,
                                                      a.arena.n_q_heads, a.arena.n_kv_heads);
   return hipGetLastError();
 }

@@ -10,109 +10,43 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 namespace {
 typedef PlanRowTile RowTile;
-typedef PlanKeyedItem Keyed;
 
-// Splits each row tile's visible key range [0, kv_hi) into chunks so that the items of one kernel
-// have similar cost and there are about `target` of them per KV head.  All row tiles of an entry use
-// the same chunk boundaries (multiples of kv_tile): the workgroups that walk one chunk of one entry
-// read the same K/V tiles, so they are made neighbours in launch order (`group` = true) and, running
-// at the same time on the XCD of their KV head, fetch each tile from HBM once and from L2 after that.
-void cut_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk, bool group,
-               int32_t wave_slots, int32_t item_cost, std::vector<Keyed>& keyed, std::vector<int64_t>& cost, std::vector<DkItem>* items,
-               std::vector<DkMerge>* merges, int64_t* part_rows) {
+// Work items of the streaming kernel: each entry's visible key range [0, kv_hi) is cut into nearly equal chunks
+// (multiples of kv_tile) so that there are about `target` items per KV head and none is shorter than min_chunk;
+// longest first.  Entries whose range is cut get partial rows and a merge record.
+void cut_stream_items(const std::vector<RowTile>& tiles, int32_t kv_tile, int32_t target, int32_t min_chunk,
+                      std::vector<DkItem>* items, std::vector<DkMerge>* merges, int64_t* part_rows) {
   if (tiles.empty()) return;
   int64_t total = 0;
-  int32_t longest = 0;
-  for (const RowTile& t : tiles) {
-    total += t.kv_hi;
-    longest = std::max(longest, t.kv_hi);
-  }
+  for (const RowTile& t : tiles) total += t.kv_hi;
   int64_t chunk = std::max<int64_t>(min_chunk, (total + target - 1) / target);
   chunk = (chunk + kv_tile - 1) / kv_tile * kv_tile;
-  if (group && wave_slots > 0) {
-    // Tile kernel: pick the chunk length by a small cost model instead.  `wave_slots` workgroups of a KV
-    // head run at a time, so n items take ceil(n / wave_slots) rounds; a round lasts as long as an item,
-    // (work / n) key tiles plus the fixed cost of an item (pipeline ramp, output store; `item_cost` key
-    // tiles).  Splitting finer shortens the rounds but adds rounds, fixed costs and partial rows to merge;
-    // what matters most is landing on a whole number of rounds.
-    const double fixed = (double)item_cost;
-    const double work = (double)total / kv_tile;
-    double best = 0;
-    int64_t best_chunk = 0;
-    for (int32_t k = 1; k <= 512; k += (k < 16 ? 1 : k < 64 ? 4 : 16)) {
-      int64_t cand = ((longest + k - 1) / k + kv_tile - 1) / kv_tile * kv_tile;
-      if (cand < min_chunk) break;
-      int64_t n = 0;
-      for (size_t b = 0; b < tiles.size();) {
-        size_t e = b;
-        int32_t hi_max = 0;
-        while (e < tiles.size() && tiles[e].entry == tiles[b].entry) hi_max = std::max(hi_max, tiles[e++].kv_hi);
-        n += (int64_t)(e - b) * ((hi_max + cand - 1) / cand);
-        b = e;
-      }
-      const double rounds = (double)((n + wave_slots - 1) / wave_slots);
-      const double cost = rounds * (work / (double)n + fixed);
-      if (best_chunk == 0 || cost < best * 0.999) {
-        best = cost;
-        best_chunk = cand;
-      }
+  const size_t first = items->size();
+  for (const RowTile& t : tiles) {
+    int32_t ns = (int32_t)((t.kv_hi + chunk - 1) / chunk);
+    if (ns > 1 && t.kv_hi - (int64_t)(ns - 1) * chunk < chunk / 4) --ns;  // no sliver at the end
+    const int64_t each = ((t.kv_hi + ns - 1) / ns + kv_tile - 1) / kv_tile * kv_tile;
+    ns = (int32_t)((t.kv_hi + each - 1) / each);
+    int32_t part0 = -1;
+    if (ns > 1) {
+      part0 = (int32_t)*part_rows;
+      *part_rows += (int64_t)ns * t.nrows;
+      merges->push_back({t.entry, t.row0, t.nrows, part0, ns, {0, 0, 0}});
     }
-    if (best_chunk) chunk = best_chunk;
-  }
-
-  keyed.clear();
-  // tiles of one entry are consecutive in `tiles`
-  for (size_t b = 0; b < tiles.size();) {
-    size_t e = b;
-    int32_t hi_max = 0;
-    while (e < tiles.size() && tiles[e].entry == tiles[b].entry) hi_max = std::max(hi_max, tiles[e++].kv_hi);
-    int32_t nsplit = (int32_t)((hi_max + chunk - 1) / chunk);
-    // avoid a last split that is only a sliver
-    if (nsplit > 1 && hi_max - (int64_t)(nsplit - 1) * chunk < chunk / 4) --nsplit;
-    const int64_t each = ((hi_max + nsplit - 1) / nsplit + kv_tile - 1) / kv_tile * kv_tile;
-    const size_t first = keyed.size();
-    for (size_t k = b; k < e; ++k) {
-      const RowTile& t = tiles[k];
-      int32_t ns = (int32_t)((t.kv_hi + each - 1) / each);
-      if (ns > 1 && t.kv_hi - (int64_t)(ns - 1) * each < each / 4) --ns;  // the previous chunk takes the sliver
-      int32_t part0 = -1;
-      if (ns > 1) {
-        part0 = (int32_t)*part_rows;
-        *part_rows += (int64_t)ns * t.nrows;
-        merges->push_back({t.entry, t.row0, t.nrows, part0, ns, {0, 0, 0}});
-      }
-      for (int32_t sp = 0; sp < ns; ++sp) {
-        DkItem it{};
-        it.entry = t.entry;
-        it.row0 = t.row0;
-        it.nrows = t.nrows;
-        it.kv_lo = (int32_t)(sp * each);
-        it.kv_hi = sp + 1 == ns ? t.kv_hi : (int32_t)((sp + 1) * each);
-        it.part_row0 = ns > 1 ? part0 + sp * t.nrows : -1;
-        keyed.push_back({it, 0, sp});
-      }
+    for (int32_t sp = 0; sp < ns; ++sp) {
+      DkItem it{};
+      it.entry = t.entry;
+      it.row0 = t.row0;
+      it.nrows = t.nrows;
+      it.kv_lo = (int32_t)(sp * each);
+      it.kv_hi = sp + 1 == ns ? t.kv_hi : (int32_t)((sp + 1) * each);
+      it.part_row0 = ns > 1 ? part0 + sp * t.nrows : -1;
+      items->push_back(it);
     }
-    // cost of each (entry, chunk) group
-    cost.assign((size_t)nsplit + 1, 0);
-    for (size_t k = first; k < keyed.size(); ++k)
-      cost[keyed[k].split] += (int64_t)(keyed[k].it.kv_hi - keyed[k].it.kv_lo) * keyed[k].it.nrows;
-    for (size_t k = first; k < keyed.size(); ++k) keyed[k].group_cost = cost[keyed[k].split];
-    b = e;
   }
-  // longest first, so the tail of the launch is made of the cheapest items
-  if (group) {
-    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-      if (a.group_cost != b.group_cost) return a.group_cost > b.group_cost;
-      if (a.it.entry != b.it.entry) return a.it.entry < b.it.entry;
-      if (a.split != b.split) return a.split < b.split;
-      return a.it.row0 > b.it.row0;
-    });
-  } else {
-    std::stable_sort(keyed.begin(), keyed.end(), [](const Keyed& a, const Keyed& b) {
-      return (int64_t)(a.it.kv_hi - a.it.kv_lo) * a.it.nrows > (int64_t)(b.it.kv_hi - b.it.kv_lo) * b.it.nrows;
-    });
-  }
-  for (const Keyed& k : keyed) items->push_back(k.it);
+  std::stable_sort(items->begin() + (std::ptrdiff_t)first, items->end(), [](const DkItem& a, const DkItem& b) {
+    return (int64_t)(a.kv_hi - a.kv_lo) * a.nrows > (int64_t)(b.kv_hi - b.kv_lo) * b.nrows;
+  });
 }
 
 // The streaming kernel runs one workgroup per compute unit, and a workgroup walks a chain of units
@@ -159,34 +93,146 @@ void chain_units(const std::vector<DkItem>& items, const PlanConfig& cfg, std::v
     std::push_heap(heap.begin(), heap.end(), later);
   }
 }
-// The tile kernel runs `slots` workgroups per KV head, each walking a chain of items.  The items arrive in launch
-// order (grouped by (entry, key chunk), costliest group first) and each joins the chain that is free first, which is
-// what a hardware dispatcher would do with one workgroup per item -- so the row tiles of a group still run at the
-// same time and share their K/V tiles through L2 -- but without a workgroup start per item.
-void chain_tile_items(const std::vector<DkItem>& items, int32_t kv_tile, int32_t slots, int32_t item_cost,
-                      std::vector<std::pair<double, int32_t>>& heap, std::vector<int32_t>& tail,
-                      std::vector<int32_t>* links, int32_t* n_chains) {
-  const int32_t n = (int32_t)items.size();
-  const int32_t chains = std::min(n, std::max(slots, 1));
-  *n_chains = chains;
-  links->assign((size_t)chains + (size_t)n, -1);
-  if (n == 0) return;
-  int32_t* head = links->data();
-  int32_t* next = links->data() + chains;
-  typedef std::pair<double, int32_t> Free;  // (time at which the chain is free, chain)
-  heap.resize((size_t)chains);
-  for (int32_t c = 0; c < chains; ++c) heap[c] = {0.0, c};
-  const auto later = [](const Free& a, const Free& b) { return a > b; };
-  std::make_heap(heap.begin(), heap.end(), later);
-  tail.assign((size_t)chains, -1);
-  for (int32_t i = 0; i < n; ++i) {
-    std::pop_heap(heap.begin(), heap.end(), later);
-    Free& f = heap.back();
-    const int32_t c = f.second;
-    if (tail[c] < 0) head[c] = i; else next[tail[c]] = i;
+// Work items of the tile kernel.  `slots` workgroups per KV head each walk a chain of items; an item is a row
+// tile against a piece of its visible key range.  Costs are counted in key tiles: an item of n tiles takes
+// n + item_cost (pipeline ramp, output store).
+//   1. Pieces: with at least as many row tiles as workgroups nothing is cut; with fewer, every entry's key range
+//      is cut into floor(slots / row tiles) equal chunks, the same boundaries for all row tiles of the entry --
+//      the workgroups walking one chunk read the same K/V tiles at the same time and share them through L2.
+//   2. Longest piece first, each to the chain that is free first (pieces of one (entry, chunk) group are equally
+//      long, so they stay neighbours and start together).
+//   3. Levelling: while the busiest chain is more than a few tiles above the idlest, the tail of one of its
+//      pieces is cut off and handed to the idlest chain, sized so that the two end together.  This is what makes
+//      the chains finish together whatever the mix of lengths; it costs one more item and the partial rows of
+//      the row tile that was cut.
+// Row tiles that end up in several pieces get partial rows and a merge record.  Items are emitted chain by chain.
+void cut_tile_items(AttendPlan* p, const PlanConfig& cfg) {
+  const std::vector<RowTile>& tiles = p->tile_tiles;
+  p->tile_chains = 0;
+  if (tiles.empty()) return;
+  const int32_t kt = cfg.kv_tile;
+  const int32_t slots = std::max(cfg.tile_wave_slots, 1);
+  const int32_t fixed = std::max(cfg.tile_item_cost, 0);
+  const int32_t min_piece = std::max<int32_t>(std::max<int32_t>(1, cfg.tile_min_chunk / kt), fixed);  // tiles
+  const int32_t n_tiles = (int32_t)tiles.size();
+  const auto len_of = [&](const PlanPiece& q) { return (q.hi - q.lo + kt - 1) / kt; };
+
+  std::vector<PlanPiece>& pieces = p->pieces;
+  pieces.clear();
+  const int32_t k0 = n_tiles < slots ? slots / n_tiles : 1;
+  for (int32_t b = 0; b < n_tiles;) {  // tiles of one entry are consecutive
+    int32_t e = b, hi_max = 0;
+    while (e < n_tiles && tiles[e].entry == tiles[b].entry) hi_max = std::max(hi_max, tiles[e++].kv_hi);
+    const int32_t longest = (hi_max + kt - 1) / kt;
+    const int32_t k = std::max(1, std::min(k0, longest / min_piece));
+    const int32_t each = (longest + k - 1) / k * kt;  // keys per chunk
+    for (int32_t t = b; t < e; ++t)
+      for (int32_t lo = 0; lo < tiles[t].kv_hi;) {
+        int32_t hi = std::min(tiles[t].kv_hi, lo + each);
+        if (tiles[t].kv_hi - hi < each / 4) hi = tiles[t].kv_hi;  // no sliver at the end
+        pieces.push_back({t, lo, hi, -1});
+        lo = hi;
+      }
+    b = e;
+  }
+
+  std::vector<int32_t>& order = p->order;
+  order.resize(pieces.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int32_t)i;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+    const PlanPiece &a = pieces[x], &b = pieces[y];
+    const int32_t la = len_of(a), lb = len_of(b);
+    if (la != lb) return la > lb;
+    if (tiles[a.tile].entry != tiles[b.tile].entry) return tiles[a.tile].entry < tiles[b.tile].entry;
+    if (a.lo != b.lo) return a.lo < b.lo;
+    return tiles[a.tile].row0 > tiles[b.tile].row0;
+  });
+
+  std::vector<int32_t>&head = p->chain_head, &tail = p->chain_tail;
+  std::vector<int64_t>& load = p->chain_load;
+  head.assign((size_t)slots, -1);
+  tail.assign((size_t)slots, -1);
+  load.assign((size_t)slots, 0);
+  const auto append = [&](int32_t c, int32_t i) {
+    if (tail[c] < 0) head[c] = i; else pieces[tail[c]].next = i;
     tail[c] = i;
-    f.first += (double)((items[i].kv_hi - items[i].kv_lo + kv_tile - 1) / kv_tile + item_cost);
-    std::push_heap(heap.begin(), heap.end(), later);
+    pieces[i].next = -1;
+    load[c] += len_of(pieces[i]) + fixed;
+  };
+  {
+    typedef std::pair<double, int32_t> Free;  // (time at which the chain is free, chain)
+    std::vector<Free>& heap = p->heap;
+    heap.resize((size_t)slots);
+    for (int32_t c = 0; c < slots; ++c) heap[c] = {0.0, c};
+    const auto later = [](const Free& a, const Free& b) { return a > b; };
+    std::make_heap(heap.begin(), heap.end(), later);
+    for (int32_t i : order) {
+      std::pop_heap(heap.begin(), heap.end(), later);
+      Free& f = heap.back();
+      append(f.second, i);
+      f.first = (double)load[f.second];
+      std::push_heap(heap.begin(), heap.end(), later);
+    }
+  }
+
+  for (int32_t round = 0; round < 4 * slots; ++round) {
+    int32_t busy = 0, idle = 0;
+    for (int32_t c = 1; c < slots; ++c) {
+      if (load[c] > load[busy]) busy = c;
+      if (load[c] < load[idle]) idle = c;
+    }
+    // tiles to hand over so that both chains end together (the new item pays its fixed cost on the idle chain)
+    const int64_t give = (load[busy] - load[idle] - fixed) / 2;
+    if (give < min_piece) break;
+    int32_t donor = -1;  // the last piece of the busy chain that stays a piece after giving
+    for (int32_t i = head[busy]; i >= 0; i = pieces[i].next)
+      if (len_of(pieces[i]) >= give + min_piece) donor = i;
+    if (donor < 0) break;
+    const int32_t cut = pieces[donor].lo + (len_of(pieces[donor]) - (int32_t)give) * kt;
+    pieces.push_back({pieces[donor].tile, cut, pieces[donor].hi, -1});
+    pieces[donor].hi = cut;
+    load[busy] -= give;
+    append(idle, (int32_t)pieces.size() - 1);
+  }
+
+  // partial rows and merge records of the row tiles that were cut
+  std::vector<int32_t>&count = p->tile_pieces, &part0 = p->tile_part0;
+  count.assign((size_t)n_tiles, 0);
+  part0.assign((size_t)n_tiles, -1);
+  for (const PlanPiece& q : pieces) ++count[q.tile];
+  for (int32_t t = 0; t < n_tiles; ++t)
+    if (count[t] > 1) {
+      part0[t] = (int32_t)p->part_rows;
+      p->part_rows += (int64_t)count[t] * tiles[t].nrows;
+      p->merges.push_back({tiles[t].entry, tiles[t].row0, tiles[t].nrows, part0[t], count[t], {0, 0, 0}});
+      count[t] = 0;  // from here on: pieces of the tile emitted so far
+    } else {
+      count[t] = -1;
+    }
+
+  std::vector<int32_t>& links = p->tile_links;
+  int32_t chains = 0;
+  for (int32_t c = 0; c < slots; ++c) chains += head[c] >= 0;
+  p->tile_chains = chains;
+  links.assign((size_t)chains + pieces.size(), -1);
+  int32_t cc = 0;
+  for (int32_t c = 0; c < slots; ++c) {
+    if (head[c] < 0) continue;
+    links[cc++] = (int32_t)p->tile_items.size();
+    for (int32_t i = head[c]; i >= 0; i = pieces[i].next) {
+      const PlanPiece& q = pieces[i];
+      const RowTile& t = tiles[q.tile];
+      DkItem it{};
+      it.entry = t.entry;
+      it.row0 = t.row0;
+      it.nrows = t.nrows;
+      it.kv_lo = q.lo;
+      it.kv_hi = q.hi;
+      it.part_row0 = count[q.tile] < 0 ? -1 : part0[q.tile] + count[q.tile]++ * t.nrows;
+      const int32_t idx = (int32_t)p->tile_items.size();
+      p->tile_items.push_back(it);
+      if (pieces[i].next >= 0) links[(size_t)chains + idx] = idx + 1;
+    }
   }
 }
 }  // namespace
@@ -243,12 +289,9 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
       }
     }
   }
-  cut_items(tile_tiles, cfg.kv_tile, cfg.tile_target, cfg.tile_min_chunk, true, cfg.tile_wave_slots, cfg.tile_item_cost, p->keyed, p->cost,
-            &p->tile_items, &p->merges, &p->part_rows);
-  cut_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, false, 0, 0, p->keyed, p->cost,
-            &p->stream_items, &p->merges, &p->part_rows);
-  chain_tile_items(p->tile_items, cfg.kv_tile, cfg.tile_wave_slots, cfg.tile_item_cost, p->heap, p->tail,
-                   &p->tile_links, &p->tile_chains);
+  cut_tile_items(p, cfg);
+  cut_stream_items(stream_tiles, cfg.kv_tile, cfg.stream_target, cfg.stream_min_chunk, &p->stream_items, &p->merges,
+                   &p->part_rows);
   chain_units(p->stream_items, cfg, p->heap, p->tail, &p->stream_links, &p->stream_chains);
 
   size_t off = 0;

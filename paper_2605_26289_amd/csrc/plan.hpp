@@ -18,7 +18,6 @@ struct PlanConfig {
   int32_t tile_rows;      // packed query rows per workgroup of the tile kernel
   int32_t stream_rows;    // max packed rows handled by the streaming (small-Delta) kernel
   int32_t kv_tile;        // keys per inner step; split boundaries are multiples of it
-  int32_t tile_target;    // aimed number of items per KV head, tile kernel (when tile_wave_slots is 0)
   int32_t tile_wave_slots;  // tile-kernel workgroups of one KV head that run at a time (its share of the CUs)
   int32_t stream_target;  // same, streaming kernel
   int32_t tile_min_chunk, stream_min_chunk;  // smallest key range worth its own item
@@ -32,10 +31,11 @@ struct PlanConfig {
 struct PlanRowTile {
   int32_t entry, row0, nrows, kv_hi;
 };
-struct PlanKeyedItem {
-  DkItem it;
-  int64_t group_cost;
-  int32_t split;
+// A piece of a row tile's key range on its way to becoming a work item of the tile kernel.
+struct PlanPiece {
+  int32_t tile;    // index of its row tile
+  int32_t lo, hi;  // key positions
+  int32_t next;    // next piece of the same chain, -1 at the end
 };
 
 // A plan object may be reused from call to call: build_plan() clears it but keeps the capacity of its
@@ -44,10 +44,11 @@ struct AttendPlan {
   // working storage of build_plan
   std::vector<Extent> ext;
   std::vector<PlanRowTile> tile_tiles, stream_tiles;
-  std::vector<PlanKeyedItem> keyed;
-  std::vector<int64_t> cost;
   std::vector<std::pair<double, int32_t>> heap;
   std::vector<int32_t> tail;
+  std::vector<PlanPiece> pieces;
+  std::vector<int32_t> order, chain_head, chain_tail, tile_pieces, tile_part0;
+  std::vector<int64_t> chain_load;
 
   std::vector<DkEntry> entries;
   std::vector<DkSeg> segs;
