@@ -170,28 +170,82 @@ __device__ __forceinline__ void rescale_o(WaveState& st, const float (&alpha)[MB
 // kvo/vvo are the per-lane byte offsets inside the tile (row * stride + swizzled chunk), kept across
 // steps because they only change with the tile's row count or stride.
 struct TileLoads {
-  const char* gk;
-  const char* gv;
-  uint32_t lds_k, lds_v;  // LDS byte address of this wavefront's first 1 KiB block in the target stages
+  uint32_t lds_k, lds_v;  // LDS byte address of the wavefront's next 1 KiB block in the target stages
   uint32_t kvo[4], vvo[4];
 };
 
 // One wavefront moves 1 KiB HBM -> LDS, lane l landing at lds_addr + 16 l.  Issued from inline assembly
 // on purpose: the compiler then keeps no account of it and inserts no vmcnt(0) of its own in front of
 // later LDS reads; completion is awaited explicitly with wait_vmcnt<N>().
-__device__ __forceinline__ void dma16(const char* gbase, uint32_t voff, uint32_t lds_addr) {
+// The wait state that must separate the write of M0 from the load is filled with the address arithmetic
+// for the wavefront's next block (4 KiB further on in the stage), so a block costs two issue slots.
+__device__ __forceinline__ void dma16_advance(const char* gbase, uint32_t voff, uint32_t& lds_addr) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
-      "s_nop 0\n\t"
+      "s_add_i32 %0, %0, 0x1000\n\t"
       "global_load_lds_dwordx4 %1, %2"
-      :
-      : "s"(lds_addr), "v"(voff), "s"(gbase)
-      : "memory", "m0");
+      : "+s"(lds_addr)
+      : "v"(voff), "s"(gbase)
+      : "memory", "m0", "scc");
 }
+// The tile kernel's walk over an item's key positions [p, hi): like KvCursor, but the current tile lives in
+// the cursor itself (k, v, stride, cnt, pos: no copy per step) and the usual step -- another full tile of the
+// same segment -- is a compare, two pointer additions and two counter updates.
+struct TileCursor {
+  const DkSeg* segs;
+  int32_t si, se, p, hi;  // p: first position after the current tile
+  int32_t seg_end = 0;    // first position past the current segment (0: no segment loaded yet)
+  int32_t full_end = 0;   // min(seg_end, hi): a full tile fits while p + TILE_KT <= full_end
+  const char* k = nullptr;  // current tile
+  const char* v = nullptr;
+  uint32_t stride = 0;  // bytes between consecutive rows
+  uint32_t adv = 0;     // bytes from the current tile to the next one of the same segment
+  int32_t cnt = 0;      // valid rows of the current tile
+  int32_t pos = 0;      // logical position of its row 0
+
+  // Moves on to the next tile; false (and the current tile stays) when the range is exhausted.
+  __device__ __forceinline__ bool next(const Ctx& c, int g) {
+    if (p + TILE_KT <= full_end) {  // cnt stays TILE_KT, adv stays TILE_KT * stride
+      k += adv;
+      v += adv;
+      pos = p;
+      p += TILE_KT;
+      return true;
+    }
+    if (p >= hi) return false;
+    if (p >= seg_end) {
+      DkSeg s = load_desc(segs, si);
+      while (s.pos + s.len <= p && si + 1 < se) s = load_desc(segs, ++si);
+      const int32_t off = p - s.pos;
+      seg_end = s.pos + s.len;
+      full_end = min(seg_end, hi);
+      if (s.src == 0) {
+        const int64_t byte = ((int64_t)g * c.arena_cells + s.start + off) * ROW_BYTES;
+        k = c.k_arena + byte;
+        v = c.v_arena + byte;
+        stride = ROW_BYTES;
+      } else {
+        const int64_t byte = ((s.start + off) * c.n_kv_heads + g) * (int64_t)ROW_BYTES;
+        k = c.k_new + byte;
+        v = c.v_new + byte;
+        stride = (uint32_t)c.n_kv_heads * ROW_BYTES;
+      }
+    } else {
+      k += adv;
+      v += adv;
+    }
+    cnt = min(TILE_KT, full_end - p);
+    pos = p;
+    p += cnt;
+    adv = (uint32_t)cnt * stride;
+    return true;
+  }
+};
+
 template <int I>
-__device__ __forceinline__ void issue_one(const TileLoads& ld) {
-  if constexpr (I < 4) dma16(ld.gk, ld.kvo[I], ld.lds_k + I * 4096);
-  else dma16(ld.gv, ld.vvo[I - 4], ld.lds_v + (I - 4) * 4096);
+__device__ __forceinline__ void issue_one(TileLoads& ld, const TileCursor& cur) {
+  if constexpr (I < 4) dma16_advance(cur.k, ld.kvo[I], ld.lds_k);
+  else dma16_advance(cur.v, ld.vvo[I - 4], ld.lds_v);
 }
 // Per-lane offsets of the wavefront's four blocks of a tile with cnt rows: block b is rows
 // 16 b + 4 wave + lane / 16, lane l fetching the chunk that the swizzle assigns to slot l % 16.
@@ -221,7 +275,8 @@ struct FastStep {
   const u32x4 (&pp)[MB][4];
   u32x4 (&pc)[MB][4];
   WaveState& st;
-  const TileLoads& ld;
+  TileLoads& ld;
+  const TileCursor& cur;
   const float (&ms)[MB];
   float c;
   uint32_t koff, voff;
@@ -333,7 +388,7 @@ struct FastStep {
     if constexpr (I >= 1) rowsum<I - 1>();
     if constexpr ((I & 1) == 0 && I >= 2) pack<I / 2 - 1>();
     // HBM -> LDS loads of later tiles
-    if constexpr ((I & 1) == 1 && I < 16) issue_one<(I - 1) / 2>(ld);
+    if constexpr ((I & 1) == 1 && I < 16) issue_one<(I - 1) / 2>(ld, cur);
     // row maxima of the next tile
     if constexpr (I >= MAX_FIRST) run_max<I>(std::make_integer_sequence<int, 34>{});
     __builtin_amdgcn_sched_barrier(0);
@@ -402,36 +457,33 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
   bool wave_active = false;
   bf16x8 qf[MB][8];
   int limit[MB];
-  KvCursor cur{c.segs, 0, 0, 0, 0};
-  KvTile tl;  // next tile to load
+  TileCursor cur{c.segs, 0, 0, 0, 0};  // its current tile is the next one to load
   TileLoads ld;
   int ld_cnt = -1;
   uint32_t ld_stride = 0;
   // (cnt, pos) of tiles t .. t+2 of the step about to run; cnt 0 = no such tile
   int cnt0 = 0, pos0 = 0, cnt1 = 0, pos1 = 0, cnt2 = 0, pos2 = 0;
 
-  auto offsets_stale = [&]() { return tl.cnt != ld_cnt || tl.stride != ld_stride; };
+  auto offsets_stale = [&]() { return cur.cnt != ld_cnt || cur.stride != ld_stride; };
   auto refresh_offsets = [&]() {
-    ld_cnt = tl.cnt;
-    ld_stride = tl.stride;
+    ld_cnt = cur.cnt;
+    ld_stride = cur.stride;
     lane_offsets<false>(ld.kvo, wave, lane, ld_cnt, ld_stride);
     lane_offsets<true>(ld.vvo, wave, lane, ld_cnt, ld_stride);
   };
   auto aim = [&](int k_stage, int v_stage) {
-    ld.gk = tl.k;
-    ld.gv = tl.v;
     ld.lds_k = k_ring_lds + k_stage * TILE_STAGE_BYTES;
     ld.lds_v = v_ring_lds + v_stage * TILE_STAGE_BYTES;
   };
   auto issue_all = [&]() {
-    issue_one<0>(ld);
-    issue_one<1>(ld);
-    issue_one<2>(ld);
-    issue_one<3>(ld);
-    issue_one<4>(ld);
-    issue_one<5>(ld);
-    issue_one<6>(ld);
-    issue_one<7>(ld);
+    issue_one<0>(ld, cur);
+    issue_one<1>(ld, cur);
+    issue_one<2>(ld, cur);
+    issue_one<3>(ld, cur);
+    issue_one<4>(ld, cur);
+    issue_one<5>(ld, cur);
+    issue_one<6>(ld, cur);
+    issue_one<7>(ld, cur);
   };
 
   // Requests everything an item needs before its first step: Q (into registers), its first two K/V tiles
@@ -448,17 +500,17 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
     // keys at positions above this are invisible to every row of the wavefront: those tiles are skipped
     wave_max_limit = wave_active ? e.n + (min(wave_row0 + MB * 32 - 1, last_row) >> c.gshift) : -1;
     load_q<MB>(c, e, g, wave_row0, last_row, lane, qf, limit);
-    cur = KvCursor{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
+    cur = TileCursor{c.segs, e.seg_begin, e.seg_end, it.kv_lo, it.kv_hi};
     cnt0 = pos0 = cnt2 = pos2 = 0;
-    (void)cur.next(c, g, TILE_KT, tl);  // the planner never produces an empty key range
-    cnt1 = tl.cnt;  // becomes tile 0 when step -1 hands over to step 0
-    pos1 = tl.pos;
+    (void)cur.next(c, g);  // the planner never produces an empty key range
+    cnt1 = cur.cnt;  // becomes tile 0 when step -1 hands over to step 0
+    pos1 = cur.pos;
     refresh_offsets();
     aim(0, 0);
     issue_all();
-    if (cur.next(c, g, TILE_KT, tl)) {  // when the range ends the old tile stays in tl
-      cnt2 = tl.cnt;
-      pos2 = tl.pos;
+    if (cur.next(c, g)) {  // when the range ends the old tile stays current
+      cnt2 = cur.cnt;
+      pos2 = cur.pos;
     }
     if (offsets_stale()) refresh_offsets();
     aim(1, 1);
@@ -525,9 +577,9 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
     int cnt3 = 0, pos3 = 0;
     auto fetch = [&]() {
       cnt3 = 0;
-      if (cur.next(c, g, TILE_KT, tl)) {
-        cnt3 = tl.cnt;
-        pos3 = tl.pos;
+      if (cur.next(c, g)) {
+        cnt3 = cur.cnt;
+        pos3 = cur.pos;
       }
     };
     fetch();
@@ -569,8 +621,6 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
       DK_PROF_T(t1);
       const char* k_lds = k_ring + k_rd;
       const char* v_lds = v_ring + v_rd;
-      ld.gk = tl.k;
-      ld.gv = tl.v;
       ld.lds_k = k_ring_lds + k_wr;
       ld.lds_v = v_ring_lds + v_wr;
       if (!wave_active) {
@@ -610,7 +660,7 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_
       }
       DK_PROF_T(t2);
       {
-        FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, ms, c.c, koff, voff};
+        FastStep f{k_lds, v_lds, qf, sc, sn, pp, pc, st, ld, cur, ms, c.c, koff, voff};
         f.kf[0][0] = read_k_frag(k_lds, koff, 0, 0);
         f.kf[0][1] = read_k_frag(k_lds, koff, 1, 0);
         f.kf[1][0] = read_k_frag(k_lds, koff, 0, 1);
