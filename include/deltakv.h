@@ -131,6 +131,12 @@ int32_t dk_seq_alias(dk_pool* pool, int32_t donor, int32_t dst, int64_t p0, int6
  * rejected speculative tokens).  Metadata only.  Cells other slots still see are kept.
  */
 int32_t dk_seq_trim(dk_pool* pool, int32_t slot, int64_t new_len);
+/*
+ * The same for a whole batch in one call (the trim after a batched verification step): slots HOST [n_seqs]
+ * distinct, new_len HOST int64 [n_seqs].  All or nothing: DK_ERR_NO_SLOT / DK_ERR_DUP_SLOT / DK_ERR_INVALID
+ * (a new_len above the slot's length) leave every slot as it was.
+ */
+int32_t dk_seq_trim_batch(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int64_t* new_len);
 
 /*
  * kv_append: write new tokens' K and V into the slots' next cells (the cache write of
@@ -301,10 +307,14 @@ int32_t dk_prefill_groups(int32_t n_slots, const int32_t* const* tokens, const i
  *   min(len, cap) entries.  Aliased positions report the donor's cells.
  * dk_seq_gather: copy the slot's logical contents out as DEVICE [len, n_kv_heads, head_dim].
  * dk_pool_stats: cells currently allocated to live sequences / chains, and free cells.
+ * dk_seq_stats: how the slot's logical contents lie in the arena -- the number of runs of consecutive cells
+ *   (each run boundary costs the attention kernels a partly filled key tile) and the number of alias
+ *   generations behind the slot (what the constant-time alias walks).  Each pointer nullable.
  */
 int32_t dk_seq_cells(dk_pool* pool, int32_t slot, int64_t* cells_out, int64_t cap);
 int32_t dk_seq_gather(dk_pool* pool, int32_t slot, void* k_out, void* v_out, void* stream);
 int32_t dk_pool_stats(dk_pool* pool, int64_t* cells_held_out, int64_t* cells_free_out);
+int32_t dk_seq_stats(dk_pool* pool, int32_t slot, int64_t* segments_out, int64_t* chain_nodes_out);
 
 /* Kernel selection for dk_delta_attend: 0 automatic (default), 1 force the scalar reference kernel. */
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);

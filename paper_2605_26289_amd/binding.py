@@ -53,6 +53,7 @@ SIGNATURES = {
     "dk_seq_len": (C.c_int32, [C.c_void_p, C.c_int32, _I64P]),
     "dk_seq_alias": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int64]),
     "dk_seq_trim": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64]),
+    "dk_seq_trim_batch": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I64P]),
     "dk_kv_append": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_kv_reserve": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, _I32P, _I64P]),
     "dk_attend_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_int32, _I64P]),
@@ -62,6 +63,7 @@ SIGNATURES = {
                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
     "dk_seq_gather": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dk_seq_stats": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, _I64P]),
     "dk_pool_stats": (C.c_int32, [C.c_void_p, _I64P, _I64P]),
     "dk_verify_workspace_bytes": (C.c_int32, [C.c_int32, C.c_int64, C.c_int32, _I64P]),
     "dk_verify_greedy": (C.c_int32, [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
@@ -194,11 +196,24 @@ def seq_trim(pool, slot: int, new_len: int) -> None:
     _check(lib().dk_seq_trim(pool, slot, new_len), "seq_trim")
 
 
+def seq_trim_batch(pool, slots, new_len) -> None:
+    s_arr, s_p = _i32(slots)
+    n_arr = np.ascontiguousarray(new_len, dtype=np.int64)
+    _check(lib().dk_seq_trim_batch(pool, len(s_arr), s_p, n_arr.ctypes.data_as(_I64P)), "seq_trim_batch")
+
+
 def seq_cells(pool, slot: int) -> np.ndarray:
     n = seq_len(pool, slot)
     out = np.full(n, -1, dtype=np.int64)
     _check(lib().dk_seq_cells(pool, slot, out.ctypes.data_as(_I64P), n), "seq_cells")
     return out
+
+
+def seq_stats(pool, slot: int):
+    """(runs of consecutive cells, alias generations) of a slot"""
+    seg, depth = C.c_int64(), C.c_int64()
+    _check(lib().dk_seq_stats(pool, slot, C.byref(seg), C.byref(depth)), "seq_stats")
+    return seg.value, depth.value
 
 
 def pool_stats(pool):

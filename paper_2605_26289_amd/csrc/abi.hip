@@ -252,8 +252,16 @@ int32_t dk_seq_alias(dk_pool* pool, int32_t donor, int32_t dst, int64_t p0, int6
 int32_t dk_seq_trim(dk_pool* pool, int32_t slot, int64_t new_len) {
   return pool ? pool->meta.trim(slot, new_len) : DK_ERR_INVALID;
 }
+int32_t dk_seq_trim_batch(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int64_t* new_len) {
+  if (!pool) return DK_ERR_INVALID;
+  return guarded([&]() -> int32_t { return pool->meta.trim_batch(n_seqs, slots, new_len); });
+}
 int32_t dk_seq_cells(dk_pool* pool, int32_t slot, int64_t* cells_out, int64_t cap) {
   return pool ? pool->meta.cells(slot, cells_out, cap) : DK_ERR_INVALID;
+}
+int32_t dk_seq_stats(dk_pool* pool, int32_t slot, int64_t* segments_out, int64_t* chain_nodes_out) {
+  if (!pool) return DK_ERR_INVALID;
+  return guarded([&]() -> int32_t { return pool->meta.seq_stats(slot, segments_out, chain_nodes_out); });
 }
 int32_t dk_pool_stats(dk_pool* pool, int64_t* held, int64_t* free_cells) {
   return pool ? pool->meta.stats(held, free_cells) : DK_ERR_INVALID;

@@ -63,12 +63,13 @@ void GranuleAllocator::give_back(int64_t g) {
 
 // ---------------------------------------------------------------- Node
 Node::~Node() {
+  if (borrow_cap > 0 && parent) parent->tail_lent = false;  // nothing refers to the borrowed cells any more
   if (!granules.empty()) alloc->unmark_tail(granules.back());
   for (int64_t g : granules) alloc->give_back(g);
 }
 
 int64_t Node::granules_needed(int64_t extra) const {
-  const int64_t want = (len + extra + gr - 1) / gr;
+  const int64_t want = (std::max<int64_t>(0, len + extra - borrow_cap) + gr - 1) / gr;
   return std::max<int64_t>(0, want - (int64_t)granules.size());
 }
 
@@ -79,6 +80,9 @@ void Node::grow(int64_t extra) {
     if (!granules.empty()) {
       alloc->unmark_tail(granules.back());
       if (alloc->take(granules.back() + 1)) g = granules.back() + 1;
+    } else if (borrow_cap > 0) {  // continue right behind the granule the first cells were borrowed from
+      const int64_t after = (borrow_cell + borrow_cap) / gr;
+      if (alloc->take(after)) g = after;
     }
     if (g < 0) g = alloc->take_fresh();
     granules.push_back(g);
@@ -88,7 +92,7 @@ void Node::grow(int64_t extra) {
 }
 
 void Node::shrink_to(int64_t new_len) {
-  const int64_t keep = (new_len + gr - 1) / gr;
+  const int64_t keep = (std::max<int64_t>(0, new_len - borrow_cap) + gr - 1) / gr;
   if ((int64_t)granules.size() > keep) {
     alloc->unmark_tail(granules.back());
     while ((int64_t)granules.size() > keep) {
@@ -107,6 +111,12 @@ Pool::Pool(int32_t n_slots, int32_t n_session, int64_t arena_cells, int32_t gran
   for (int32_t s = n_transient_; s < n_slots; ++s) free_[1].push_back(s);
 }
 
+void Pool::set_head(Slot& s, std::shared_ptr<Node> n) {
+  if (s.head) --s.head->owners;
+  s.head = std::move(n);
+  if (s.head) ++s.head->owners;
+}
+
 int32_t Pool::acquire(int32_t region, int64_t timeout_ms, int32_t* slot_out) {
   if ((region != 0 && region != 1) || !slot_out) return ERR_INVALID;
   std::unique_lock<std::mutex> lk(mu_);
@@ -122,7 +132,7 @@ int32_t Pool::acquire(int32_t region, int64_t timeout_ms, int32_t* slot_out) {
   const int32_t s = free_[region].front();
   free_[region].pop_front();
   slots_[s].in_use = true;
-  slots_[s].head.reset();
+  set_head(slots_[s], nullptr);
   slots_[s].len = 0;
   *slot_out = s;
   return OK;
@@ -132,7 +142,7 @@ int32_t Pool::release(int32_t slot) {
   {
     std::lock_guard<std::mutex> lk(mu_);
     if (!valid(slot)) return ERR_NO_SLOT;
-    slots_[slot].head.reset();  // cells live on while an alias chain still references the node
+    set_head(slots_[slot], nullptr);  // cells live on while an alias chain still references the node
     slots_[slot].len = 0;
     slots_[slot].in_use = false;
     free_[slot >= n_transient_ ? 1 : 0].push_back(slot);
@@ -159,19 +169,56 @@ int32_t Pool::alias(int32_t donor, int32_t dst, int64_t p0, int64_t p1) {
   std::shared_ptr<Node> a = slots_[donor].head;
   while (a->base >= p1) a = a->parent;
   a->frozen = std::max(a->frozen, p1);
-  slots_[dst].head = std::make_shared<Node>(&alloc_, gr_, a, p1);
+  std::shared_ptr<Node> fresh = std::make_shared<Node>(&alloc_, gr_, a, p1);
+  // Continuing exactly at the end of a node nobody appends to any more: take over the unused rest of the
+  // granule its last cell lies in (its own last granule, or what is left of the room it borrowed itself).
+  if (p1 == a->end() && a->len > 0 && a->owners == 0 && !a->tail_lent) {
+    int64_t room_cell = -1, room = 0;
+    if (a->granules.empty()) {
+      room_cell = a->borrow_cell + a->len;
+      room = a->borrow_cap - a->len;
+    } else if ((a->len - a->borrow_cap) % gr_ != 0) {
+      const int64_t used = (a->len - a->borrow_cap) % gr_;
+      room_cell = a->granules.back() * gr_ + used;
+      room = gr_ - used;
+    }
+    if (room > 0) {
+      fresh->borrow_cell = room_cell;
+      fresh->borrow_cap = room;
+      a->tail_lent = true;
+    }
+  }
+  set_head(slots_[dst], std::move(fresh));
   slots_[dst].len = p1;
   return OK;
 }
 
 int32_t Pool::trim(int32_t slot, int64_t new_len) {
   std::lock_guard<std::mutex> lk(mu_);
+  return trim_locked(slot, new_len);
+}
+
+int32_t Pool::trim_batch(int32_t n, const int32_t* slots, const int64_t* new_len) {
+  if (n < 0 || (n > 0 && (!slots || !new_len))) return ERR_INVALID;
+  std::lock_guard<std::mutex> lk(mu_);
+  std::vector<char> seen(slots_.size(), 0);
+  for (int32_t b = 0; b < n; ++b) {
+    if (!valid(slots[b])) return ERR_NO_SLOT;
+    if (seen[slots[b]]) return ERR_DUP_SLOT;
+    seen[slots[b]] = 1;
+    if (new_len[b] < 0 || new_len[b] > slots_[slots[b]].len) return ERR_INVALID;
+  }
+  for (int32_t b = 0; b < n; ++b) (void)trim_locked(slots[b], new_len[b]);
+  return OK;
+}
+
+int32_t Pool::trim_locked(int32_t slot, int64_t new_len) {
   if (!valid(slot)) return ERR_NO_SLOT;
   Slot& s = slots_[slot];
   if (new_len < 0 || new_len > s.len) return ERR_INVALID;
   if (new_len == s.len) return OK;
   if (new_len == 0) {
-    s.head.reset();
+    set_head(s, nullptr);
     s.len = 0;
     return OK;
   }
@@ -185,7 +232,7 @@ int32_t Pool::trim(int32_t slot, int64_t new_len) {
     std::shared_ptr<Node> a = h;
     while (a->base >= new_len) a = a->parent;
     a->frozen = std::max(a->frozen, new_len);
-    s.head = std::make_shared<Node>(&alloc_, gr_, a, new_len);
+    set_head(s, std::make_shared<Node>(&alloc_, gr_, a, new_len));
   }
   s.len = new_len;
   return OK;
@@ -203,15 +250,21 @@ void Pool::resolve(const std::shared_ptr<Node>& head, int64_t len, std::vector<E
   for (auto it = parts.rbegin(); it != parts.rend(); ++it) {
     const Node* n = it->first;
     int64_t own = it->second - n->base;  // tokens of this node that are visible
-    for (size_t gi = 0; own > 0; ++gi) {
-      const int64_t take = std::min(own, n->gr);
-      const int64_t cell = n->granules[gi] * n->gr;
-      const int64_t pos = n->base + (int64_t)gi * n->gr;
+    const auto add = [&](int64_t cell, int64_t pos, int64_t take) {
       if (!out->empty() && out->back().cell + out->back().len == cell && out->back().pos + out->back().len == pos) {
         out->back().len += take;
       } else {
         out->push_back({cell, pos, take});
       }
+    };
+    if (n->borrow_cap > 0 && own > 0) {  // first cells in the rest of the parent's last granule
+      const int64_t take = std::min(own, n->borrow_cap);
+      add(n->borrow_cell, n->base, take);
+      own -= take;
+    }
+    for (size_t gi = 0; own > 0; ++gi) {
+      const int64_t take = std::min(own, n->gr);
+      add(n->granules[gi] * n->gr, n->base + n->borrow_cap + (int64_t)gi * n->gr, take);
       own -= take;
     }
   }
@@ -244,6 +297,18 @@ int32_t Pool::stats(int64_t* held, int64_t* free_cells) {
   std::lock_guard<std::mutex> lk(mu_);
   if (held) *held = (alloc_.total() - alloc_.free_count()) * gr_;
   if (free_cells) *free_cells = alloc_.free_count() * gr_;
+  return OK;
+}
+
+int32_t Pool::seq_stats(int32_t slot, int64_t* segments, int64_t* chain_nodes) {
+  std::lock_guard<std::mutex> lk(mu_);
+  if (!valid(slot)) return ERR_NO_SLOT;
+  std::vector<Extent> ext;
+  resolve(slots_[slot].head, slots_[slot].len, &ext);
+  if (segments) *segments = (int64_t)ext.size();
+  int64_t depth = 0;
+  for (const Node* n = slots_[slot].head.get(); n; n = n->parent.get()) ++depth;
+  if (chain_nodes) *chain_nodes = depth;
   return OK;
 }
 
@@ -286,7 +351,7 @@ int32_t Pool::append(int32_t n_seqs, const int32_t* slots, const int32_t* cu_del
     const int64_t cnt = n_accept ? n_accept[b] : delta;
     if (cnt == 0) continue;
     Slot& s = slots_[slots[b]];
-    if (!s.head) s.head = std::make_shared<Node>(&alloc_, gr_, nullptr, 0);
+    if (!s.head) set_head(s, std::make_shared<Node>(&alloc_, gr_, nullptr, 0));
     Node& h = *s.head;
     const int64_t old = h.len;
     h.grow(cnt);

@@ -64,7 +64,11 @@ struct Node {
   int64_t granules_needed(int64_t extra) const;  // granules an append of `extra` tokens must add
   void grow(int64_t extra);                      // caller has checked the allocator holds enough
   void shrink_to(int64_t new_len);               // own length, frees whole unused granules
-  int64_t cell_of(int64_t own_offset) const { return granules[own_offset / gr] * gr + own_offset % gr; }
+  int64_t cell_of(int64_t own_offset) const {
+    if (own_offset < borrow_cap) return borrow_cell + own_offset;
+    const int64_t o = own_offset - borrow_cap;
+    return granules[o / gr] * gr + o % gr;
+  }
 
   GranuleAllocator* alloc;
   int64_t gr;
@@ -73,6 +77,14 @@ struct Node {
   int64_t len = 0;
   int64_t frozen = 0;  // absolute position; own cells below it are visible to a child and never rewritten
   std::vector<int64_t> granules;
+  // A node that continues exactly where its parent ends, after the parent's own sequence has gone, writes its
+  // first cells into the unused rest of the parent's last granule: a turn that extends a cached conversation
+  // then stays physically contiguous with it and wastes no granule.  The room is [borrow_cell, + borrow_cap);
+  // the granule itself stays the parent's (the child keeps the parent alive).
+  int64_t borrow_cell = -1;
+  int64_t borrow_cap = 0;
+  bool tail_lent = false;  // the unused rest of this node's last granule is some child's borrow room
+  int32_t owners = 0;      // sequences whose newest node this is: they may still append to it
 };
 
 struct Slot {
@@ -95,8 +107,12 @@ class Pool {
   int32_t length(int32_t slot, int64_t* out);
   int32_t alias(int32_t donor, int32_t dst, int64_t p0, int64_t p1);
   int32_t trim(int32_t slot, int64_t new_len);
+  // Several trims at once, all or nothing (slots distinct).
+  int32_t trim_batch(int32_t n, const int32_t* slots, const int64_t* new_len);
   int32_t cells(int32_t slot, int64_t* out, int64_t cap);
   int32_t stats(int64_t* held, int64_t* free_cells);
+  // runs of consecutive cells the slot's logical view consists of, and nodes on its chain
+  int32_t seq_stats(int32_t slot, int64_t* segments, int64_t* chain_nodes);
 
   // Batched append bookkeeping: checks every slot, reserves the cells, advances the lengths and
   // reports the destination cell of every appended token (dst[t] = -1 for tokens not appended) and,
@@ -117,6 +133,8 @@ class Pool {
 
  private:
   bool valid(int32_t slot) const { return slot >= 0 && slot < (int32_t)slots_.size() && slots_[slot].in_use; }
+  int32_t trim_locked(int32_t slot, int64_t new_len);
+  void set_head(Slot& s, std::shared_ptr<Node> n);
   static void resolve(const std::shared_ptr<Node>& head, int64_t len, std::vector<Extent>* out);
 
   std::mutex mu_;

@@ -79,6 +79,9 @@ class DevicePool:
     def trim(self, slot: int, new_len: int) -> None:
         dk.seq_trim(self.handle, slot, new_len)
 
+    def trim_batch(self, slots: Sequence[int], new_len: Sequence[int]) -> None:
+        dk.seq_trim_batch(self.handle, slots, new_len)
+
     def cells(self, slot: int):
         return dk.seq_cells(self.handle, slot)
 

@@ -329,3 +329,18 @@ def test_long_extents_under_interleaved_growth():
         runs.append(1 + int((np.diff(c) != 1).sum()))
     assert max(runs) <= 8, runs
     dk.pool_destroy(p)
+
+
+def test_trim_batch_is_all_or_nothing():
+    p = _pool(n_slots=4, arena_cells=4096)
+    a, b, c = (dk.seq_acquire(p, 0) for _ in range(3))
+    dk.kv_reserve(p, [a, b, c], [0, 50, 90, 100])
+    dk.seq_trim_batch(p, [a, c], [20, 0])
+    assert [dk.seq_len(p, s) for s in (a, b, c)] == [20, 40, 0]
+    for slots, lens, err in (([a, b], [10, 41], "INVALID"), ([a, a], [1, 2], "DUP_SLOT"), ([a, 3], [1, 0], "NO_SLOT")):
+        with pytest.raises(dk.DeltaKVError) as e:
+            dk.seq_trim_batch(p, slots, lens)
+        assert e.value.name == err
+        assert [dk.seq_len(p, s) for s in (a, b, c)] == [20, 40, 0]   # nothing moved
+    dk.seq_trim_batch(p, [], [])
+    dk.pool_destroy(p)

@@ -106,6 +106,75 @@ def test_shared_preamble_survives_and_forks_split_nodes():
     b.close()
 
 
+def test_35_turn_workflow_stays_contiguous_and_wastes_no_granules():
+    """The per-turn procedure of Alg. 1 on the 35-turn coding workflow (Delta ~ U{200..1200}, context growing to
+    about 24k tokens): every turn is a fresh sequence that aliases the cached conversation and appends its delta.
+    The delta's first cells go into the unused rest of the previous turn's last granule, so the conversation stays
+    one run of consecutive cells (no ragged key tile per turn for the kernels), the arena holds no more than one
+    granule beyond the logical cells, and the alias walk is as deep as there are turns, not tokens."""
+    from paper_2605_26289_amd import workloads as wl
+    w = wl.config3()
+    gran = 256
+    total = w.turns[-1].n_past[0] + w.turns[-1].delta[0]
+    desc = dk.PoolDesc(40, 36, total + 64 * gran, gran, 32, 8, 128, dk.BF16, 256 * 10, 256 * 20, 256 * 30, 1 << 20)
+    pool = dk.pool_create(desc)
+    radix = dk.radix_create(pool, total + 1000, 1)
+    tokens = np.random.default_rng(3).integers(0, 50000, size=total).tolist()
+    worst_segments = 0
+    for t, turn in enumerate(w.turns):
+        n = turn.n_past[0] + turn.delta[0]
+        slot = dk.seq_acquire(pool, 0)
+        n_past = dk.radix_begin_turn(radix, slot, tokens[:n])
+        assert n_past == turn.n_past[0]
+        dk.kv_reserve(pool, [slot], [0, n - n_past])
+        segments, depth = dk.seq_stats(pool, slot)
+        worst_segments = max(worst_segments, segments)
+        assert depth == t + 1                      # one alias generation per turn
+        assert dk.radix_save(radix, slot, tokens[:n])
+        dk.seq_release(pool, slot)
+        held, _free = dk.pool_stats(pool)
+        assert n <= held < n + gran                # internal fragmentation: less than one granule in all
+    assert worst_segments == 1                     # the whole conversation is one run of consecutive cells
+    cells = dk.seq_cells(pool, dk.seq_acquire(pool, 0))  # (an empty slot: just exercises the probe)
+    assert cells.size == 0
+    dk.radix_destroy(radix)
+    assert dk.pool_stats(pool)[0] == 0
+    dk.pool_destroy(pool)
+
+
+def test_borrowed_tail_room_is_never_shared_between_two_continuations():
+    """Two sequences continue the same released conversation at its end: only one may write into the unused rest of
+    its last granule, and a continuation of a conversation whose own sequence is still alive never does."""
+    gran = 16
+    desc = dk.PoolDesc(6, 2, 4096, gran, 8, 2, 64, dk.BF16, 256 * 10, 256 * 20, 256 * 30, 1 << 20)
+    pool = dk.pool_create(desc)
+    a = dk.seq_acquire(pool, 0)
+    dk.kv_reserve(pool, [a], [0, 40])              # 40 cells: two and a half granules
+    keep = dk.seq_acquire(pool, 1)
+    dk.seq_alias(pool, a, keep, 0, 40)             # a session sequence keeps the cells alive
+    b = dk.seq_acquire(pool, 0)
+    dk.seq_alias(pool, a, b, 0, 40)                # a is still alive and may append: b must not borrow
+    cb = dk.kv_reserve(pool, [b], [0, 5])
+    ca = dk.kv_reserve(pool, [a], [0, 5])
+    assert set(cb.tolist()).isdisjoint(ca.tolist())
+    base = dk.seq_cells(pool, a)
+    assert ca.tolist() == list(range(base[39] + 1, base[39] + 6))    # a itself continues in place
+    dk.seq_release(pool, a)
+    dk.seq_release(pool, b)
+    # now nobody appends to the 40-cell node any more... but a's five extra cells follow it in the same granule,
+    # so continuations of the first 40 positions get fresh cells
+    c, d = dk.seq_acquire(pool, 0), dk.seq_acquire(pool, 0)
+    dk.seq_alias(pool, keep, c, 0, 40)
+    dk.seq_alias(pool, keep, d, 0, 40)
+    cc = dk.kv_reserve(pool, [c], [0, 12])
+    cd = dk.kv_reserve(pool, [d], [0, 12])
+    shared = set(dk.seq_cells(pool, keep).tolist())
+    assert set(cc.tolist()).isdisjoint(cd.tolist())
+    assert shared.isdisjoint(cc.tolist()) and shared.isdisjoint(cd.tolist())
+    assert dk.seq_cells(pool, c)[:40].tolist() == dk.seq_cells(pool, keep).tolist()
+    dk.pool_destroy(pool)
+
+
 def test_radix_errors():
     pool = _pool(4, 2)
     radix = dk.radix_create(pool, 100)
