@@ -12,6 +12,11 @@ Workloads (synthetic stand-ins for the paper's agentic traces, see paper_2605_26
   c4_512   the same with Delta = 512 for every slot                                        (MFMA)
   c3       35-turn coding workflow, Delta U[200,1200]; reports the final turn               (MFMA)
   c2       5-turn agent conversation, Delta = 150 (launch-latency bound)
+  mixed    one scheduler iteration: 4 prefill chunks sized by the chunking rule + 60 decode / verify slots
+  c2_alg1, c3_alg1   the same conversations through the radix-cached per-turn procedure (Alg. 1): every turn
+           acquires a sequence, aliases the cached prefix, appends and attends only the delta, saves, releases
+  alg2     the speculative step (Alg. 2) on c5's batch with nothing read back between its stages: append the
+           k+1 tokens, verify attention, on-device argmax + accept, asynchronous copy of the kept counts, trim
 """
 from __future__ import annotations
 
@@ -32,7 +37,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c5", choices=["c5", "c4", "c4_512", "c3", "c2"])
+    ap.add_argument("--workload", default="c5",
+                    choices=["c5", "c4", "c4_512", "c3", "c2", "mixed", "c2_alg1", "c3_alg1", "alg2"])
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="planner tuning passed to dk_set_tuning on every pool (repeatable)")
+    ap.add_argument("--host-profile", action="store_true",
+                    help="instead of the benchmark, print where the host time of a step goes (plan, upload, launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-extra", action="store_true",
@@ -69,6 +79,9 @@ class Scenario:
         self.gen = gen
         cells = w.cells_needed() + 512 * (w.n_slots + 2)
         self.pool = DevicePool(w.n_slots, cells, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype)
+        for name, value in TUNING:
+            from paper_2605_26289_amd import binding as _dk
+            _dk.set_tuning(self.pool.handle, name, value)
         self.slots = [self.pool.acquire() for _ in range(w.n_slots)]
         self.host_kv = {}
         self.keep = set(self.slots[:keep_host_slots])
@@ -89,6 +102,7 @@ class Scenario:
                     self._ingest(s, d)
         t = self.turn
         t.slots = np.asarray(t.slots, dtype=np.int32)  # marshalled once, not per step
+        t.n_past = np.asarray(t.n_past, dtype=np.int64)
         for s, n in zip(t.slots, t.n_past):
             assert self.pool.length(s) == n, (s, self.pool.length(s), n)
         total = sum(t.delta)
@@ -124,8 +138,7 @@ class Scenario:
             done += c
 
     def _rewind(self):
-        for s, n in zip(self.turn.slots, self.turn.n_past):
-            self.pool.trim(s, n)
+        self.pool.trim_batch(self.turn.slots, self.turn.n_past)
 
     def step(self):
         t = self.turn
@@ -182,7 +195,16 @@ def make_workload(name, drafts=8):
         return wl.config3(), -1
     if name == "c2":
         return wl.config2(), -1
+    if name == "mixed":
+        from paper_2605_26289_amd import binding as dk
+        # 4 slots prefill at once: the chunking rule of Sec. 3.2 cuts the 4096-token batch into 1024-token chunks
+        return wl.mixed_prefill_decode(chunk=dk.prefill_chunk(4096, 4)), -1
     raise ValueError(name)
+
+
+TUNING = []  # (name, value) pairs applied to every pool (--tune)
+TRAFFIC_SOURCE = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command, kept in profiles/hbm_traffic.txt " \
+                 "with the commit they were taken at (not re-measured in this run)"
 
 
 def measured_traffic(name):
@@ -202,20 +224,27 @@ def measured_traffic(name):
 
 
 def roofline_for(name, flops, nbytes, kernel_ms):
+    """kernel_ms: median duration of the call's attention work (all kernels of dk_delta_attend), from HIP events the
+    library records on the launch stream."""
     sec = kernel_ms * 1e-3
     traffic = measured_traffic(name)
+    hbm = nbytes / sec / 1e9
+    mfma = flops / sec / 1e12
     if name in ("c5", "c2"):
-        ach = nbytes / sec / 1e9
-        return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic}
-    ach = flops / sec / 1e12
-    return {"bound": "mfma", "achieved": round(ach, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic}
+        return {"bound": "hbm", "achieved": round(hbm, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(hbm / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": TRAFFIC_SOURCE}
+    r = {"bound": "mfma", "achieved": round(mfma, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+         "frac": round(mfma / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic, "traffic_source": TRAFFIC_SOURCE}
+    if name == "mixed":  # both kernels in one call: the streaming part is bound by HBM, the tile part by the MFMA pipe
+        r["hbm_frac_of_whole_call"] = round(hbm / HBM_PEAK_GBS, 4)
+    return r
 
 
 def verify_leg(w, vocab, steps, warmup):
     """Greedy verification of the batch's k+1 rows per slot over synthetic bf16 logits (the step after the verify
-    attention in the paper's Alg. 2).  Times dk_verify_greedy alone with HIP events on the launch stream."""
+    attention in the paper's Alg. 2).  Times dk_verify_greedy alone with HIP events on the launch stream.  The calls
+    rotate over enough distinct logits buffers that consecutive calls cannot be served from the 256 MB Infinity
+    Cache: every logit comes from HBM."""
     import torch
     from paper_2605_26289_amd import binding as dk
     t = w.turns[-1]
@@ -223,8 +252,11 @@ def verify_leg(w, vocab, steps, warmup):
     rows, n = int(cu[-1]), len(t.delta)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed + 1000)
-    logits = torch.randn((rows, vocab), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    am = logits.float().argmax(dim=1).to(torch.int32)  # only used to plant drafts that will be accepted
+    one = rows * vocab * 2
+    n_buf = max(2, -(-(640 << 20) // one))  # at least 640 MB in rotation
+    logits = [torch.randn((rows, vocab), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+              for _ in range(n_buf)]
+    am = logits[0].float().argmax(dim=1).to(torch.int32)  # only used to plant drafts that will be accepted
     toks = torch.randint(0, vocab, (rows,), generator=gen, device="cuda", dtype=torch.int32)
     accept = torch.rand((rows,), generator=gen, device="cuda") < 0.8
     toks[1:] = torch.where(accept[1:], am[:-1], toks[1:])
@@ -232,23 +264,196 @@ def verify_leg(w, vocab, steps, warmup):
     keep = torch.empty(n, dtype=torch.int32, device="cuda")
     nxt = torch.empty(n, dtype=torch.int32, device="cuda")
     ws = torch.empty(dk.verify_workspace_bytes(rows, vocab, dk.BF16), dtype=torch.uint8, device="cuda")
-    run = lambda: dk.verify_greedy(n, rows, cu_d, logits, dk.BF16, vocab, vocab, toks, keep, nxt, ws)  # noqa: E731
-    for _ in range(warmup):
-        run()
+    run = lambda i: dk.verify_greedy(n, rows, cu_d, logits[i % n_buf], dk.BF16, vocab, vocab, toks, keep, nxt, ws)  # noqa: E731
+    for i in range(max(warmup, n_buf)):
+        run(i)
+    run(0)
+    torch.cuda.synchronize()
+    kept = round(float(keep.float().mean().item()), 2)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for a, b in ev:
+    for i, (a, b) in enumerate(ev):
         a.record()
-        run()
+        run(i + 1)
         b.record()
     torch.cuda.synchronize()
-    ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
-    nbytes = rows * vocab * 2
-    ach = nbytes / (ms * 1e-3) / 1e9
-    return {"workload": f"greedy verification of {n} slots x {rows // max(n, 1)} rows, vocab {vocab}, bf16 logits",
+    ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+    ach = one / (ms * 1e-3) / 1e9
+    return {"workload": f"greedy verification of {n} slots x {rows // max(n, 1)} rows, vocab {vocab}, bf16 logits, "
+                        f"{n_buf} logits buffers in rotation ({n_buf * one >> 20} MiB)",
             "rows": rows, "ms": round(ms, 4), "rows_per_s": round(rows / (ms * 1e-3), 1),
-            "mean_kept_tokens": round(float(keep.float().mean().item()), 2),
+            "mean_kept_tokens": kept,
             "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}}
+                         "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": measured_traffic("verify"),
+                         "traffic_source": TRAFFIC_SOURCE}}
+
+
+def alg1_leg(w, reps, warmup):
+    """The radix-cached per-turn procedure of the paper's Alg. 1 over a whole conversation: per turn, acquire a
+    transient sequence, alias the longest cached prefix (metadata only), append and attend only the delta, save the
+    turn into the prefix cache, release the sequence.  Reports throughput over all turns and how the conversation lies
+    in the arena at its last turn (runs of consecutive cells, alias generations, cells held against logical cells)."""
+    import torch
+    from paper_2605_26289_amd import DevicePool
+    from paper_2605_26289_amd import binding as dk
+    from paper_2605_26289_amd import workloads as wl
+    sh = w.shape
+    tokens = wl.token_stream(w)
+    prompts = []
+    if w.history and w.history[0]:
+        prompts.append(w.history[0])  # the system prompt is ingested (and cached) first, as its own turn
+    prompts += [t.n_past[0] + t.delta[0] for t in w.turns]
+    n_turns, total = len(prompts), prompts[-1]
+    pool = DevicePool(n_turns + 6, total + 4096, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype,
+                      n_session_slots=n_turns + 2)
+    for name, value in TUNING:
+        dk.set_tuning(pool.handle, name, value)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    dt = pool.torch_dtype
+    biggest = max(b - a for a, b in zip([0] + prompts[:-1], prompts))
+    q = torch.randn((biggest, sh.n_q_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    k = torch.randn((biggest, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    v = torch.randn((biggest, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    out = torch.empty_like(q)
+    toks = np.asarray(tokens, dtype=np.int32)
+    layout = {}
+
+    def conversation(record=False):
+        radix = dk.radix_create(pool.handle, total + 1024, 1)
+        past = []
+        for t, n in enumerate(prompts):
+            slot = pool.acquire(0)
+            n_past = dk.radix_begin_turn(radix, slot, toks[:n])
+            past.append(n_past)
+            d = n - n_past
+            cu = np.asarray([0, d], dtype=np.int32)
+            pool.append([slot], cu, k[:d], v[:d])
+            pool.attend([slot], cu, q[:d], sh.scale, out=out[:d])
+            if record and t == n_turns - 1:
+                seg, depth = dk.seq_stats(pool.handle, slot)
+                layout.update(segments_last_turn=seg, alias_generations=depth)
+            dk.radix_save(radix, slot, toks[:n])
+            pool.release(slot)
+        if record:
+            held, _ = dk.pool_stats(pool.handle)
+            layout.update(cells_held=held, cells_logical=total, n_past_per_turn=past)
+        torch.cuda.synchronize()
+        dk.radix_destroy(radix)
+
+    for _ in range(warmup):
+        conversation()
+    conversation(record=True)
+    dk.set_attend_timing(pool.handle, min(256, n_turns))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        conversation()
+    wall = (time.perf_counter() - t0) / reps
+    kern = dk.attend_times(pool.handle)  # the last conversation's turns, oldest first
+    dk.set_attend_timing(pool.handle, 0)
+    new_tokens = sum(n - p for n, p in zip(prompts, layout["n_past_per_turn"]))
+    first, last = w.turns[0], w.turns[-1]
+    res = {"workload": f"{w.name} through Alg. 1 (acquire, radix alias, append delta, attend, save, release)",
+           "turns": n_turns, "new_tokens": int(new_tokens), "cached_tokens_skipped": int(sum(layout["n_past_per_turn"])),
+           "tokens_per_s": round(new_tokens / wall, 1), "ms_per_conversation": round(wall * 1e3, 4),
+           "ms_per_turn": round(wall * 1e3 / n_turns, 4),
+           "last_turn": {"n_past": int(layout["n_past_per_turn"][-1]), "delta": int(prompts[-1] - layout["n_past_per_turn"][-1]),
+                         "attend_kernel_ms": round(float(kern[-1]), 4) if len(kern) else None},
+           "segments_last_turn": int(layout["segments_last_turn"]), "alias_generations": int(layout["alias_generations"]),
+           "cells_held": int(layout["cells_held"]), "cells_logical": int(layout["cells_logical"]),
+           "fragmentation": round(layout["cells_held"] / max(layout["cells_logical"], 1) - 1.0, 4)}
+    if len(kern):
+        fl = attend_flops(res["last_turn"]["n_past"], res["last_turn"]["delta"], sh.n_q_heads, sh.head_dim)
+        res["last_turn"]["achieved_tflops"] = round(fl / (float(kern[-1]) * 1e-3) / 1e12, 1)
+    pool.close()
+    return res
+
+
+def alg2_leg(w, vocab, steps, warmup):
+    """One speculative step of the paper's Alg. 2 per timed step, on one stream, with nothing read back between its
+    stages: kv_append of all k+1 tokens, verify attention over them (appended mode), greedy verification of the
+    (synthetic) logits on the device, an asynchronous copy of the kept counts to pinned memory.  The trim that drops
+    the rejected tokens is deferred to the start of the next step, when the host reads the counts it needs anyway to
+    build the next batch; it then rewinds the slots so that every step sees the same state."""
+    import torch
+    from paper_2605_26289_amd import DevicePool
+    from paper_2605_26289_amd import binding as dk
+    sh = w.shape
+    t = w.turns[-1]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed + 7)
+    cells = w.cells_needed() + 512 * (w.n_slots + 2)
+    pool = DevicePool(w.n_slots, cells, sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype)
+    for name, value in TUNING:
+        dk.set_tuning(pool.handle, name, value)
+    dt = pool.torch_dtype
+    slots = np.asarray([pool.acquire() for _ in range(w.n_slots)], dtype=np.int32)
+    for s, h in zip(slots, w.history):
+        done = 0
+        while done < h:
+            c = min(65536, h - done)
+            kv = torch.randn((c, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+            pool.append([s], [0, c], kv, kv)
+            done += c
+    cu = np.concatenate([[0], np.cumsum(t.delta)]).astype(np.int32)
+    rows, n = int(cu[-1]), len(t.delta)
+    n_past = np.asarray(t.n_past, dtype=np.int64)
+    q = torch.randn((rows, sh.n_q_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    kn = torch.randn((rows, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    vn = torch.randn((rows, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
+    out = torch.empty_like(q)
+    logits = torch.randn((rows, vocab), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    am = logits.float().argmax(dim=1).to(torch.int32)
+    toks = torch.randint(0, vocab, (rows,), generator=gen, device="cuda", dtype=torch.int32)
+    accept = torch.rand((rows,), generator=gen, device="cuda") < 0.8
+    toks[1:] = torch.where(accept[1:], am[:-1], toks[1:])
+    cu_d = torch.from_numpy(cu).cuda()
+    keep_d = torch.empty(n, dtype=torch.int32, device="cuda")
+    next_d = torch.empty(n, dtype=torch.int32, device="cuda")
+    keep_h = torch.empty(n, dtype=torch.int32, pin_memory=True)
+    vws = torch.empty(dk.verify_workspace_bytes(rows, vocab, dk.BF16), dtype=torch.uint8, device="cuda")
+    copied = torch.cuda.Event()
+    slots_sorted = slots[np.asarray(t.slots)]
+    pool.append(slots_sorted, cu, kn, vn)
+    pool.ensure_workspace(slots_sorted, cu, False)
+    pool.trim_batch(slots_sorted, n_past)
+    pending = [False]
+
+    def settle():
+        """The deferred part of the previous step: read the kept counts, drop the rejected tokens."""
+        if pending[0]:
+            copied.synchronize()
+            pool.trim_batch(slots_sorted, n_past + keep_h.numpy())
+            pool.trim_batch(slots_sorted, n_past)  # benchmark only: every step starts from the same state
+            pending[0] = False
+
+    def step():
+        settle()
+        pool.append(slots_sorted, cu, kn, vn)
+        pool.attend(slots_sorted, cu, q, sh.scale, out=out)
+        dk.verify_greedy(n, rows, cu_d, logits, dk.BF16, vocab, vocab, toks, keep_d, next_d, vws)
+        keep_h.copy_(keep_d, non_blocking=True)
+        copied.record()
+        pending[0] = True
+
+    for _ in range(warmup):
+        step()
+    settle()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    settle()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    kept = float(keep_h.float().mean().item())
+    res = {"workload": f"Alg. 2 step on {w.name}: kv_append(k+1) + verify attention + on-device argmax/accept + "
+                       "async copy of kept counts + deferred trim",
+           "slots": n, "rows": rows, "ms_per_step": round(wall * 1e3, 4), "verified_tokens_per_s": round(rows / wall, 1),
+           "kept_tokens_per_s": round(kept * n / wall, 1), "mean_kept_tokens": round(kept, 2),
+           "host_syncs_inside_step": 0}
+    pool.close()
+    return res
 
 
 def other_configs(steps, warmup):
@@ -259,17 +464,20 @@ def other_configs(steps, warmup):
     out = {}
     c3 = wl.config3()
     median_turn = int(np.argsort([t.delta[0] * (t.n_past[0] + 1) for t in c3.turns])[len(c3.turns) // 2])
+    mixed, _ = make_workload("mixed")
     for key, w, turn in (("c1_fp32_single", wl.config1(), -1), ("c2_agent_5turn_final", wl.config2(), -1),
                          ("c3_coding_median_turn", c3, median_turn), ("c3_coding_final_turn", c3, -1),
-                         ("c4_multi_agent", wl.config4(), -1)):
+                         ("c4_multi_agent", wl.config4(), -1), ("mixed_prefill_decode", mixed, -1)):
         sc = Scenario(w, turn)
-        step_s, kern_ms, _ = sc.run(steps, warmup)
+        step_s, _, kern_ms = sc.run(steps, warmup)  # median kernel time
         fl, by = sc.algorithmic()
         out[key] = {"new_tokens_per_step": int(sc.total), "cached_tokens": int(sum(sc.turn.n_past)),
                     "tokens_per_s": round(sc.total / step_s, 1), "ms_per_step": round(step_s * 1e3, 4),
                     "attend_kernel_ms": round(kern_ms, 4),
                     "achieved_tflops": round(fl / (kern_ms * 1e-3) / 1e12, 1),
-                    "achieved_gbs": round(by / (kern_ms * 1e-3) / 1e9, 1)}
+                    "mfma_frac": round(fl / (kern_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "achieved_gbs": round(by / (kern_ms * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(by / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del sc
         torch.cuda.empty_cache()
     return out
@@ -278,11 +486,13 @@ def other_configs(steps, warmup):
 def cpu_baseline(sc, budget_s):
     """Times the fp64 oracle, as it stands, on a bounded sample of the same batch; also checks the GPU rows."""
     import oracle
+    cores = len(os.sched_getaffinity(0))
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        threads = len(os.sched_getaffinity(0))
+        threadpool_limits = None
+        blas_threads = cores
     t = sc.turn
     sh = sc.sh
     done_tokens, spent, worst_abs, worst_rel, used, checked = 0, 0.0, 0.0, 0.0, 0, 0
@@ -321,10 +531,78 @@ def cpu_baseline(sc, budget_s):
             break
     if not done_tokens:
         return None, None
-    base = {"value": round(done_tokens / spent, 2), "unit": "new tokens/s", "cores": int(threads), "kind": "oracle",
+    one_thread = None
+    if threadpool_limits is not None:  # per-core figure: the same oracle calls with the BLAS pinned to one thread
+        spent1, tokens1 = 0.0, 0
+        with threadpool_limits(limits=1):
+            for b, s in enumerate(t.slots):
+                if s not in sc.keep or t.delta[b] == 0 or spent1 > min(4.0, budget_s / 3):
+                    continue
+                lo, hi = int(sc.cu[b]), int(sc.cu[b + 1])
+                kc, vc = sc.host_cache(s)
+                kc, vc = kc[: t.n_past[b]], vc[: t.n_past[b]]
+                rows = None if hi - lo <= 32 else sorted(set(np.linspace(0, hi - lo - 1, 16).astype(int).tolist()))
+                t0 = time.perf_counter()
+                oracle.delta_attend(q[lo:hi], kc, vc, kn[lo:hi], vn[lo:hi], sh.scale, rows)
+                spent1 += time.perf_counter() - t0
+                tokens1 += (hi - lo) if rows is None else len(rows)
+        if tokens1:
+            one_thread = round(tokens1 / spent1, 2)
+    base = {"value": round(done_tokens / spent, 2), "unit": "new tokens/s", "cores": int(min(cores, blas_threads)),
+            "host_cores_available": int(cores), "blas_threads": int(blas_threads), "one_thread_value": one_thread,
+            "kind": "oracle",
             "sample": f"{checked} new-token rows of {used} slot(s) of the same batch, {passes} pass(es), "
                       f"fp64 NumPy, {spent:.1f} s"}
     return base, {"max_abs": worst_abs, "max_rel": worst_rel, "rows": checked}
+
+
+def host_profile(args):
+    """Where the host time of a step goes, for a workload whose step is shorter than its launch path (c2 by default):
+    wall time per Python-level call, and inside the library per phase (dk_host_times)."""
+    import torch
+    from paper_2605_26289_amd import binding as dk
+    name = args.workload if args.workload in ("c2", "c3", "c4", "c4_512", "c5", "mixed") else "c2"
+    w, turn = make_workload(name, args.drafts)
+    sc = Scenario(w, turn)
+    t = sc.turn
+    for _ in range(max(args.warmup, 20)):
+        sc.step()
+    torch.cuda.synchronize()
+    n = max(args.steps, 200)
+    dk.host_times(sc.pool.handle, reset=True)
+    acc = {"kv_append": [], "delta_attend": [], "trim_batch": []}
+    t_all = time.perf_counter()
+    for _ in range(n):
+        a = time.perf_counter()
+        if t.staged:
+            sc.pool.attend(t.slots, sc.cu, sc.q, sc.sh.scale, sc.k_new, sc.v_new, out=sc.out)
+            b = time.perf_counter()
+            sc.pool.append(t.slots, sc.cu, sc.k_new, sc.v_new, sc.n_accept)
+            c = time.perf_counter()
+            acc["delta_attend"].append(b - a)
+            acc["kv_append"].append(c - b)
+        else:
+            sc.pool.append(t.slots, sc.cu, sc.k_new, sc.v_new)
+            b = time.perf_counter()
+            sc.pool.attend(t.slots, sc.cu, sc.q, sc.sh.scale, out=sc.out)
+            c = time.perf_counter()
+            acc["kv_append"].append(b - a)
+            acc["delta_attend"].append(c - b)
+        sc._rewind()
+        acc["trim_batch"].append(time.perf_counter() - c)
+    host_wall = time.perf_counter() - t_all
+    torch.cuda.synchronize()
+    total_wall = time.perf_counter() - t_all
+    inside, calls = dk.host_times(sc.pool.handle)
+    _, _, kern_ms = sc.run(50, 5)
+    print(json.dumps({"workload": w.name, "steps": n, "host_us_per_step": round(host_wall / n * 1e6, 2),
+                      "wall_us_per_step_with_gpu_drain": round(total_wall / n * 1e6, 2),
+                      "attend_kernel_us": round(kern_ms * 1e3, 2),
+                      "python_call_us_median": {k: round(float(np.median(v)) * 1e6, 2) for k, v in acc.items()},
+                      "python_call_us_mean": {k: round(float(np.mean(v)) * 1e6, 2) for k, v in acc.items()},
+                      "python_call_us_max": {k: round(float(np.max(v)) * 1e6, 2) for k, v in acc.items()},
+                      "inside_library_us": {k: round(v / n, 2) for k, v in inside.items()},
+                      "calls": {"delta_attend": calls[0], "kv_append": calls[1]}}))
 
 
 def main():
@@ -348,6 +626,20 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_per_launch": n, "launches": 5}))
         return
+    for item in args.tune:
+        name, _, value = item.partition("=")
+        TUNING.append((name, float(value)))
+    from paper_2605_26289_amd import workloads as wl
+    if args.host_profile:
+        host_profile(args)
+        return
+    if args.workload in ("c2_alg1", "c3_alg1"):
+        w = wl.config2() if args.workload == "c2_alg1" else wl.config3()
+        print(json.dumps(alg1_leg(w, max(3, args.steps // 2), 2)))
+        return
+    if args.workload == "alg2":
+        print(json.dumps(alg2_leg(wl.config5(k_draft=args.drafts), args.vocab, args.steps, args.warmup)))
+        return
     w, turn = make_workload(args.workload, args.drafts)
     keep = 0 if args.no_cpu_baseline else min(w.n_slots, 32)
     sc = Scenario(w, turn, keep_host_slots=keep)
@@ -361,10 +653,10 @@ def main():
                    "n_q_heads": sc.sh.n_q_heads, "n_kv_heads": sc.sh.n_kv_heads, "head_dim": sc.sh.head_dim,
                    "cached_tokens": int(sum(sc.turn.n_past)), "mode": "staged" if sc.turn.staged else "appended",
                    "step": "delta_attend + kv_append + trim"},
-        "attend_kernel_ms": round(kern_mean_ms, 4), "attend_kernel_ms_median": round(kern_med_ms, 4),
-        "attend_only_tokens_per_s": round(sc.total / (kern_mean_ms * 1e-3), 1),
+        "attend_kernel_ms": round(kern_med_ms, 4), "attend_kernel_ms_mean": round(kern_mean_ms, 4),
+        "attend_only_tokens_per_s": round(sc.total / (kern_med_ms * 1e-3), 1),
         "algorithmic": {"flops": int(flops), "bytes": int(nbytes)},
-        "roofline": roofline_for(args.workload, flops, nbytes, kern_mean_ms),
+        "roofline": roofline_for(args.workload, flops, nbytes, kern_med_ms),
     }
     if not args.no_extra and args.workload == "c5":
         # The secondary legs run before the CPU leg on purpose: ten seconds of host-only work let the GPU drop
@@ -372,7 +664,7 @@ def main():
         # second regime in the same run: Delta = 512 on every slot of the multi-agent batch (MFMA-bound)
         w2, t2 = make_workload("c4_512")
         sc2 = Scenario(w2, t2)
-        s2, km2, _ = sc2.run(args.steps, max(args.warmup, 10))
+        s2, _, km2 = sc2.run(args.steps, max(args.warmup, 10))
         f2, b2 = sc2.algorithmic()
         result["extra"] = {"workload": w2.name + "_delta512", "new_tokens_per_step": int(sc2.total),
                            "tokens_per_s": round(sc2.total / s2, 1), "ms_per_step": round(s2 * 1e3, 4),
@@ -380,7 +672,9 @@ def main():
         del sc2
         torch.cuda.empty_cache()
         result["verify"] = verify_leg(w, args.vocab, args.steps, args.warmup)
+        result["alg2_step"] = alg2_leg(w, args.vocab, args.steps, args.warmup)
         result["other_configs"] = other_configs(max(5, args.steps // 2), 3)
+        result["alg1"] = {"c2": alg1_leg(wl.config2(), 10, 2), "c3": alg1_leg(wl.config3(), 3, 1)}
     if not args.no_cpu_baseline:
         base, parity = cpu_baseline(sc, args.cpu_seconds)
         result["cpu_baseline"] = base

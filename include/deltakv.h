@@ -344,6 +344,23 @@ int32_t dk_set_attend_timing(dk_pool* pool, int32_t n_calls);
 int32_t dk_attend_times(dk_pool* pool, float* ms_out, int32_t cap, int32_t* n_out);
 int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out);
 
+/*
+ * Host time the launching calls of this pool have spent, by phase, in microseconds since the last reset
+ * (a profiling probe: a few clock reads per call).  us_out HOST double [DK_HOST_PHASES] indexed by the
+ * enum below, calls_out HOST int64 [2]: number of dk_delta_attend(_noalloc) and of dk_kv_append calls.
+ * Each pointer nullable; reset != 0 clears the sums.
+ */
+enum {
+  DK_HOST_PLAN = 0,          /* delta_attend: argument checks, resolving slots to segments, cutting work items */
+  DK_HOST_STAGE = 1,         /* delta_attend: descriptors copied into the staging buffer */
+  DK_HOST_UPLOAD = 2,        /* delta_attend: hipMemcpyAsync of the descriptors + its event */
+  DK_HOST_LAUNCH = 3,        /* delta_attend: kernel launches (and timing events when recording) */
+  DK_HOST_APPEND_BOOK = 4,   /* kv_append: bookkeeping (cells reserved, lengths advanced) */
+  DK_HOST_APPEND_LAUNCH = 5, /* kv_append: table upload if any, kernel launch */
+  DK_HOST_PHASES = 6
+};
+int32_t dk_host_times(dk_pool* pool, int32_t reset, double* us_out, int64_t* calls_out);
+
 const char* dk_strerror(int32_t status);
 int32_t dk_last_hip_error(dk_pool* pool);
 

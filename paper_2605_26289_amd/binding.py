@@ -85,6 +85,7 @@ SIGNATURES = {
     "dk_set_attend_timing": (C.c_int32, [C.c_void_p, C.c_int32]),
     "dk_attend_times": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float), C.c_int32, _I32P]),
     "dk_last_attend_ms": (C.c_int32, [C.c_void_p, C.POINTER(C.c_float)]),
+    "dk_host_times": (C.c_int32, [C.c_void_p, C.c_int32, C.POINTER(C.c_double), _I64P]),
     "dk_strerror": (C.c_char_p, [C.c_int32]),
     "dk_last_hip_error": (C.c_int32, [C.c_void_p]),
 }
@@ -403,6 +404,17 @@ def last_attend_ms(pool) -> float:
     out = C.c_float()
     _check(lib().dk_last_attend_ms(pool, C.byref(out)), "last_attend_ms", pool)
     return out.value
+
+
+HOST_PHASES = ("plan", "stage", "upload", "launch", "append_bookkeeping", "append_launch")
+
+
+def host_times(pool, reset: bool = False):
+    """({phase: microseconds}, (delta_attend calls, kv_append calls)) since the last reset"""
+    us = (C.c_double * len(HOST_PHASES))()
+    calls = (C.c_int64 * 2)()
+    _check(lib().dk_host_times(pool, int(reset), us, calls), "host_times")
+    return dict(zip(HOST_PHASES, list(us))), (calls[0], calls[1])
 
 
 def strerror(status: int) -> str:

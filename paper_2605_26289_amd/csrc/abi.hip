@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -29,6 +30,17 @@ struct Staging {
   char* host = nullptr;
   hipEvent_t done = nullptr;
   bool in_flight = false;
+};
+
+struct PhaseClock {
+  std::chrono::steady_clock::time_point t = std::chrono::steady_clock::now();
+  // microseconds since the last call (or construction)
+  double lap() {
+    const auto now = std::chrono::steady_clock::now();
+    const double us = std::chrono::duration<double, std::micro>(now - t).count();
+    t = now;
+    return us;
+  }
 };
 
 // Exceptions must not cross the C boundary: host containers may throw std::bad_alloc.
@@ -57,6 +69,9 @@ struct dk_pool {
   std::vector<hipEvent_t> ev0, ev1;  // ring of start/stop events around the attention kernels
   int64_t ev_calls = 0;              // calls recorded since timing was switched on
   int32_t last_hip = 0;
+  // host time spent inside launching calls, by phase (see dk_host_times)
+  double host_us[DK_HOST_PHASES] = {};
+  int64_t host_calls[2] = {0, 0};  // dk_delta_attend*, dk_kv_append
   std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring, dev_meta and plan)
   dk::AttendPlan plan;   // reused from call to call so that steady-state planning allocates nothing
 
@@ -272,6 +287,7 @@ int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const 
   if (!pool) return DK_ERR_INVALID;
   return guarded([&]() -> int32_t {
     std::lock_guard<std::mutex> launch(pool->launch_mu);
+    PhaseClock clk;
     const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
     if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
     const bool inline_cells = total <= dk::KV_INLINE_MAX_TOKENS;
@@ -287,9 +303,12 @@ int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const 
       return status;
     };
     hipStream_t st = (hipStream_t)stream;
+    pool->host_us[DK_HOST_APPEND_BOOK] += clk.lap();
+    ++pool->host_calls[1];
     if (inline_cells) {
       hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
                                                   (int32_t)total, k_new, v_new, st);
+      pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
       return e == hipSuccess ? DK_OK : undo(pool->hip_fail(e));
     }
     for (int64_t base = 0; base < total; base += per_launch) {
@@ -306,6 +325,7 @@ int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const 
                                            (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
       if (e != hipSuccess) return undo(pool->hip_fail(e));
     }
+    pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
     return DK_OK;
   });
 }
@@ -381,6 +401,7 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   if ((k_new == nullptr) != (v_new == nullptr)) return DK_ERR_INVALID;
   std::lock_guard<std::mutex> launch(pool->launch_mu);
   const bool staged = k_new != nullptr;
+  PhaseClock clk;
   dk::AttendPlan& plan = pool->plan;
   dk::PlanConfig cfg = pool->cfg;
   // the MFMA kernels take the row maximum before scaling, which needs a positive finite scale
@@ -393,12 +414,20 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   if (plan.total_tokens == 0) return DK_OK;
   if (!q || !out) return DK_ERR_INVALID;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)plan.total_bytes) return DK_ERR_WORKSPACE;
+  pool->host_us[DK_HOST_PLAN] += clk.lap();
 
   hipStream_t st = (hipStream_t)stream;
-  Staging* s;
-  int32_t rc = pool->stage(plan.blob_bytes, &s);
-  if (rc != DK_OK) return rc;
-  char* h = s->host;
+  // Small descriptor blobs travel inside the kernel arguments; larger ones go through a staging buffer into
+  // the workspace.
+  const bool inline_blob = plan.blob_bytes <= (size_t)dk::INLINE_BLOB_BYTES;
+  dk::InlineBlob blob_args{};
+  char* h = (char*)&blob_args;
+  Staging* s = nullptr;
+  if (!inline_blob) {
+    const int32_t rc = pool->stage(plan.blob_bytes, &s);
+    if (rc != DK_OK) return rc;
+    h = s->host;
+  }
   auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
   put(plan.off_entries, plan.entries.data(), plan.entries.size() * sizeof(DkEntry));
   put(plan.off_segs, plan.segs.data(), plan.segs.size() * sizeof(DkSeg));
@@ -407,15 +436,22 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
   put(plan.off_links, plan.stream_links.data(), plan.stream_links.size() * sizeof(int32_t));
   put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
-  rc = pool->upload(s, workspace, plan.blob_bytes, st);
-  if (rc != DK_OK) return rc;
+  pool->host_us[DK_HOST_STAGE] += clk.lap();
+  if (!inline_blob) {
+    const int32_t rc = pool->upload(s, workspace, plan.blob_bytes, st);
+    if (rc != DK_OK) return rc;
+  }
+  pool->host_us[DK_HOST_UPLOAD] += clk.lap();
 
+  // where the kernels find the descriptors: in the workspace, or at these offsets of their own arguments
   char* ws = (char*)workspace;
+  const uintptr_t desc = inline_blob ? 0 : (uintptr_t)ws;
   dk::AttendArgs a;
+  a.inline_blob = inline_blob ? &blob_args : nullptr;
   a.arena = pool->view();
-  a.entries = (const DkEntry*)(ws + plan.off_entries);
+  a.entries = (const DkEntry*)(desc + plan.off_entries);
   a.n_entries = (int32_t)plan.entries.size();
-  a.segs = (const DkSeg*)(ws + plan.off_segs);
+  a.segs = (const DkSeg*)(desc + plan.off_segs);
   a.q = q;
   a.k_new = k_new;
   a.v_new = v_new;
@@ -437,17 +473,17 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
     e = dk::launch_attend_ref(a, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   } else {
-    e = dk::launch_attend_tile(a, (const DkItem*)(ws + plan.off_tile), (const int32_t*)(ws + plan.off_tile_links),
+    e = dk::launch_attend_tile(a, (const DkItem*)(desc + plan.off_tile), (const int32_t*)(desc + plan.off_tile_links),
                                plan.tile_chains, st);
     if (e != hipSuccess) return pool->hip_fail(e);
     int32_t stream_rows = 0;
     for (const DkItem& it : plan.stream_items) stream_rows = std::max(stream_rows, it.nrows);
-    e = dk::launch_attend_stream(a, (const DkItem*)(ws + plan.off_stream), (const int32_t*)(ws + plan.off_links),
+    e = dk::launch_attend_stream(a, (const DkItem*)(desc + plan.off_stream), (const int32_t*)(desc + plan.off_links),
                                  plan.stream_chains, stream_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
     int32_t max_rows = 0;
     for (const DkMerge& mg : plan.merges) max_rows = std::max(max_rows, mg.nrows);
-    e = dk::launch_attend_merge(a, (const DkMerge*)(ws + plan.off_merges), (int32_t)plan.merges.size(), max_rows, st);
+    e = dk::launch_attend_merge(a, (const DkMerge*)(desc + plan.off_merges), (int32_t)plan.merges.size(), max_rows, st);
     if (e != hipSuccess) return pool->hip_fail(e);
   }
   if (timing) {  // the interval covers every kernel of the call, the merge of split key ranges included
@@ -455,6 +491,8 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
     if (e != hipSuccess) return pool->hip_fail(e);
     ++pool->ev_calls;
   }
+  pool->host_us[DK_HOST_LAUNCH] += clk.lap();
+  ++pool->host_calls[0];
   return DK_OK;
 }
 
@@ -650,6 +688,22 @@ int32_t dk_last_attend_ms(dk_pool* pool, float* ms_out) {
   int32_t rc = dk_attend_times(pool, ms_out, 1, &n);
   if (rc != DK_OK) return rc;
   return n == 1 ? DK_OK : DK_ERR_INVALID;
+}
+
+int32_t dk_host_times(dk_pool* pool, int32_t reset, double* us_out, int64_t* calls_out) {
+  if (!pool) return DK_ERR_INVALID;
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  if (us_out)
+    for (int i = 0; i < DK_HOST_PHASES; ++i) us_out[i] = pool->host_us[i];
+  if (calls_out) {
+    calls_out[0] = pool->host_calls[0];
+    calls_out[1] = pool->host_calls[1];
+  }
+  if (reset) {
+    for (double& x : pool->host_us) x = 0.0;
+    pool->host_calls[0] = pool->host_calls[1] = 0;
+  }
+  return DK_OK;
 }
 
 const char* dk_strerror(int32_t status) {

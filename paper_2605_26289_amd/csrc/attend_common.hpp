@@ -35,6 +35,23 @@ __device__ __forceinline__ T load_desc(const T* base, int idx) {
   return out;
 }
 
+// Kernel-argument form of the descriptor blob: the kernels take it as their FIRST argument, so in the inline
+// instantiation it starts the kernel-argument segment and descriptor "pointers" are byte offsets from there.
+template <bool INLINE> struct BlobArg;
+template <> struct BlobArg<true> { InlineBlob blob; };
+template <> struct BlobArg<false> { char unused; };
+
+template <bool INLINE, typename T>
+__device__ __forceinline__ const T* resolve_desc(const T* p) {
+  if constexpr (INLINE) {
+    typedef const __attribute__((address_space(4))) char* const_char_ptr;
+    const_char_ptr base = (const_char_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    return (const T*)((uintptr_t)base + (uintptr_t)p);
+  } else {
+    return p;
+  }
+}
+
 struct Ctx {
   const DkEntry* entries;
   const DkSeg* segs;

@@ -157,9 +157,17 @@ constexpr int STREAM_LDS_BYTES = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
 
 // MB = 32-row blocks per unit: 1 when no unit of the launch has more than 32 packed rows (Delta <= 32 / G:
 // decode and short verify steps then skip the second, all-padding block), else 2.
-template <int MB>
-__global__ __launch_bounds__(256, 1) void attend_stream_kernel(Ctx c, const int32_t* links, int n_chains) {
+// INLINE: the descriptors arrive inside the kernel arguments (first argument) and the descriptor pointers are byte
+// offsets into them; otherwise they point into the uploaded workspace.
+template <int MB, bool INLINE>
+__global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> blob, Ctx c, const int32_t* links,
+                                                               int n_chains) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  (void)blob;
+  c.entries = resolve_desc<INLINE>(c.entries);
+  c.segs = resolve_desc<INLINE>(c.segs);
+  c.items = resolve_desc<INLINE>(c.items);
+  links = resolve_desc<INLINE>(links);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // The workgroup walks its chain of units (item, KV head); the planner balanced the chains against
@@ -297,18 +305,24 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const 
   static std::once_flag attr_once;
   static hipError_t attr_status = hipSuccess;
   std::call_once(attr_once, [] {
-    attr_status = hipFuncSetAttribute((const void*)attend_stream_kernel<1>,
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
-    if (attr_status == hipSuccess)
-      attr_status = hipFuncSetAttribute((const void*)attend_stream_kernel<2>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
+    const void* kernels[4] = {(const void*)attend_stream_kernel<1, false>, (const void*)attend_stream_kernel<1, true>,
+                              (const void*)attend_stream_kernel<2, false>, (const void*)attend_stream_kernel<2, true>};
+    for (const void* k : kernels)
+      if (attr_status == hipSuccess)
+        attr_status = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
   });
   if (attr_status != hipSuccess) return attr_status;
   const Ctx c = make_ctx(a, items);
-  if (max_rows <= 32)
-    attend_stream_kernel<1><<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
-  else
-    attend_stream_kernel<2><<<dim3((unsigned)n_chains), 256, STREAM_LDS_BYTES, stream>>>(c, links, n_chains);
+  const dim3 grid((unsigned)n_chains);
+  if (a.inline_blob) {
+    BlobArg<true> blob{*a.inline_blob};
+    if (max_rows <= 32) attend_stream_kernel<1, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains);
+    else attend_stream_kernel<2, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains);
+  } else {
+    const BlobArg<false> none{0};
+    if (max_rows <= 32) attend_stream_kernel<1, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains);
+    else attend_stream_kernel<2, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains);
+  }
   return hipGetLastError();
 }
 

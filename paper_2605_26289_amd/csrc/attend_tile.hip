@@ -431,8 +431,17 @@ __device__ __forceinline__ void plain_s(const char* k_lds, const bf16x8 (&qf)[MB
 // link is negative.  The chains are the same for every KV head; the planner balanced them.
 // Between two items of a chain the loads of the next item (descriptors, Q, its first two K/V tiles) are
 // requested before the output of the finished one is stored, so they overlap with the store phase.
-__global__ __launch_bounds__(256, 1) void attend_tile_kernel(Ctx c, const int32_t* links, int n_chains) {
+// INLINE: the descriptors arrive inside the kernel arguments (first argument) and the descriptor pointers are
+// byte offsets into them; otherwise they point into the uploaded workspace.
+template <bool INLINE>
+__global__ __launch_bounds__(256, 1) void attend_tile_kernel(BlobArg<INLINE> blob, Ctx c, const int32_t* links,
+                                                             int n_chains) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  (void)blob;
+  c.entries = resolve_desc<INLINE>(c.entries);
+  c.segs = resolve_desc<INLINE>(c.segs);
+  c.items = resolve_desc<INLINE>(c.items);
+  links = resolve_desc<INLINE>(links);
   const int g = blockIdx.x % c.n_kv_heads;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -759,13 +768,21 @@ hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, const in
   static std::once_flag attr_once;
   static hipError_t attr_status = hipSuccess;
   std::call_once(attr_once, [] {
-    attr_status = hipFuncSetAttribute((const void*)attend_tile_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      TILE_LDS_BYTES);
+    attr_status = hipFuncSetAttribute((const void*)attend_tile_kernel<false>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, TILE_LDS_BYTES);
+    if (attr_status == hipSuccess)
+      attr_status = hipFuncSetAttribute((const void*)attend_tile_kernel<true>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TILE_LDS_BYTES);
   });
   if (attr_status != hipSuccess) return attr_status;
   const Ctx c = make_ctx(a, items);
-  attend_tile_kernel<<<dim3((unsigned)n_chains * a.arena.n_kv_heads), 256, TILE_LDS_BYTES, stream>>>(c, links,
-                                                                                                      n_chains);
+  const dim3 grid((unsigned)n_chains * a.arena.n_kv_heads);
+  if (a.inline_blob) {
+    BlobArg<true> blob{*a.inline_blob};
+    attend_tile_kernel<true><<<grid, 256, TILE_LDS_BYTES, stream>>>(blob, c, links, n_chains);
+  } else {
+    attend_tile_kernel<false><<<grid, 256, TILE_LDS_BYTES, stream>>>(BlobArg<false>{0}, c, links, n_chains);
+  }
   return hipGetLastError();
 }
 

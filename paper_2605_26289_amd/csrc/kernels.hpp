@@ -28,7 +28,18 @@ constexpr int32_t KV_INLINE_MAX_TOKENS = 896;
 hipError_t launch_kv_scatter_inline(const ArenaView& a, void* k_arena, void* v_arena, const int64_t* cell_of_host,
                                     int32_t n_tok, const void* k_new, const void* v_new, hipStream_t stream);
 
+// Descriptors of at most this many bytes are passed to the kernels inside their arguments instead of being
+// uploaded first: a short turn then costs no host-to-device copy (and no staging buffer).
+constexpr int32_t INLINE_BLOB_BYTES = 3072;
+struct InlineBlob {
+  uint32_t w[INLINE_BLOB_BYTES / 4];
+};
+
 struct AttendArgs {
+  // Host copy of the call's descriptor blob if it travels in the kernel arguments (then `entries`, `segs` and
+  // every descriptor pointer handed to a launcher are byte offsets into the blob), else nullptr (then they are
+  // device pointers).
+  const InlineBlob* inline_blob = nullptr;
   ArenaView arena;
   const DkEntry* entries;
   int32_t n_entries;

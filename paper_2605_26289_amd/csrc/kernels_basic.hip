@@ -140,15 +140,33 @@ template <> struct VEC<__bf16> {
   }
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(64) void attend_ref_kernel(const DkEntry* __restrict__ entries, int32_t n_entries,
-                                                        const DkSeg* __restrict__ segs, const T* __restrict__ q,
+// The first argument of the attention kernels: the descriptor blob itself when it is small enough to travel in
+// the kernel arguments (descriptor pointers are then byte offsets from the start of the argument segment).
+template <bool INLINE> struct BlobParam;
+template <> struct BlobParam<true> { InlineBlob blob; };
+template <> struct BlobParam<false> { char unused; };
+template <bool INLINE, typename P>
+__device__ __forceinline__ const P* from_blob(const P* p) {
+  if constexpr (INLINE) {
+    typedef const __attribute__((address_space(4))) char* const_char_ptr;
+    return (const P*)((uintptr_t)(const_char_ptr)__builtin_amdgcn_kernarg_segment_ptr() + (uintptr_t)p);
+  } else {
+    return p;
+  }
+}
+
+template <typename T, int D, bool INLINE>
+__global__ __launch_bounds__(64) void attend_ref_kernel(BlobParam<INLINE> blob, const DkEntry* entries, int32_t n_entries,
+                                                        const DkSeg* segs, const T* __restrict__ q,
                                                         const T* __restrict__ k_arena, const T* __restrict__ v_arena,
                                                         const T* __restrict__ k_new, const T* __restrict__ v_new,
                                                         T* __restrict__ out, float* __restrict__ lse, float scale,
                                                         int32_t n_q_heads, int32_t n_kv_heads, int64_t arena_cells) {
   __shared__ float qs[D];
   __shared__ float red[64][D + 1];
+  (void)blob;
+  entries = from_blob<INLINE>(entries);
+  segs = from_blob<INLINE>(segs);
   const int lane = threadIdx.x;
   const int tok = blockIdx.x / n_q_heads;
   const int h = blockIdx.x - tok * n_q_heads;
@@ -232,11 +250,19 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream) {
   if (a.total_tokens <= 0) return hipSuccess;
   const ArenaView& v = a.arena;
   dim3 grid((unsigned)((int64_t)a.total_tokens * v.n_q_heads));
-#define DK_REF(T, D)                                                                                              \
-  attend_ref_kernel<T, D><<<grid, 64, 0, stream>>>(a.entries, a.n_entries, a.segs, (const T*)a.q,               \
-                                                   (const T*)v.k_arena, (const T*)v.v_arena, (const T*)a.k_new,  \
-                                                   (const T*)a.v_new, (T*)a.out, a.lse, a.scale, v.n_q_heads,    \
-                                                   v.n_kv_heads, v.arena_cells)
+#define DK_REF(T, D)                                                                                            \
+  do {                                                                                                          \
+    if (a.inline_blob)                                                                                          \
+      attend_ref_kernel<T, D, true><<<grid, 64, 0, stream>>>(                                                   \
+          BlobParam<true>{*a.inline_blob}, a.entries, a.n_entries, a.segs, (const T*)a.q, (const T*)v.k_arena,  \
+          (const T*)v.v_arena, (const T*)a.k_new, (const T*)a.v_new, (T*)a.out, a.lse, a.scale, v.n_q_heads,    \
+          v.n_kv_heads, v.arena_cells);                                                                         \
+    else                                                                                                        \
+      attend_ref_kernel<T, D, false><<<grid, 64, 0, stream>>>(                                                  \
+          BlobParam<false>{0}, a.entries, a.n_entries, a.segs, (const T*)a.q, (const T*)v.k_arena,              \
+          (const T*)v.v_arena, (const T*)a.k_new, (const T*)a.v_new, (T*)a.out, a.lse, a.scale, v.n_q_heads,    \
+          v.n_kv_heads, v.arena_cells);                                                                         \
+  } while (0)
   if (v.dtype == 0 && v.head_dim == 64) DK_REF(float, 64);
   else if (v.dtype == 0 && v.head_dim == 128) DK_REF(float, 128);
   else if (v.dtype == 1 && v.head_dim == 64) DK_REF(__bf16, 64);
@@ -258,14 +284,17 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream) {
 // ---------------------------------------------------------------------------------------------
 constexpr int MERGE_ROWS = 4;  // rows per wavefront; a workgroup of four wavefronts covers 16 rows
 
-template <int D>
-__global__ __launch_bounds__(256) void attend_merge_kernel(const DkMerge* __restrict__ merges,
-                                                           const DkEntry* __restrict__ entries,
+template <int D, bool INLINE>
+__global__ __launch_bounds__(256) void attend_merge_kernel(BlobParam<INLINE> blob, const DkMerge* merges,
+                                                           const DkEntry* entries,
                                                            const float* __restrict__ parts,
                                                            const float* __restrict__ parts_ml, __bf16* __restrict__ out,
                                                            float* __restrict__ lse, int32_t n_q_heads,
                                                            int32_t n_kv_heads) {
   static_assert(D == 128, "two floats per lane");
+  (void)blob;
+  merges = from_blob<INLINE>(merges);
+  entries = from_blob<INLINE>(entries);
   const DkMerge mg = merges[blockIdx.x];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -366,8 +395,14 @@ hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32
   if (a.arena.head_dim != 128 || max_rows <= 0) return hipErrorInvalidValue;
   const int rows_per_block = 4 * MERGE_ROWS;
   dim3 grid((unsigned)n_merges, (unsigned)a.arena.n_kv_heads, (unsigned)((max_rows + rows_per_block - 1) / rows_per_block));
-  attend_merge_kernel<128><<<grid, 256, 0, stream>>>(merges, a.entries, a.parts, a.parts_ml, (__bf16*)a.out, a.lse,
-                                                     a.arena.n_q_heads, a.arena.n_kv_heads);
+  if (a.inline_blob)
+    attend_merge_kernel<128, true><<<grid, 256, 0, stream>>>(BlobParam<true>{*a.inline_blob}, merges, a.entries, a.parts,
+                                                             a.parts_ml, (__bf16*)a.out, a.lse, a.arena.n_q_heads,
+                                                             a.arena.n_kv_heads);
+  else
+    attend_merge_kernel<128, false><<<grid, 256, 0, stream>>>(BlobParam<false>{0}, merges, a.entries, a.parts,
+                                                              a.parts_ml, (__bf16*)a.out, a.lse, a.arena.n_q_heads,
+                                                              a.arena.n_kv_heads);
   return hipGetLastError();
 }
 

@@ -296,20 +296,21 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
 
   size_t off = 0;
   p->off_entries = off;
-  off = align_up(off + p->entries.size() * sizeof(DkEntry), 256);
+  off = align_up(off + p->entries.size() * sizeof(DkEntry), 16);
   p->off_segs = off;
-  off = align_up(off + p->segs.size() * sizeof(DkSeg), 256);
+  off = align_up(off + p->segs.size() * sizeof(DkSeg), 16);
   p->off_tile = off;
-  off = align_up(off + p->tile_items.size() * sizeof(DkItem), 256);
+  off = align_up(off + p->tile_items.size() * sizeof(DkItem), 16);
   p->off_tile_links = off;
-  off = align_up(off + p->tile_links.size() * sizeof(int32_t), 256);
+  off = align_up(off + p->tile_links.size() * sizeof(int32_t), 16);
   p->off_stream = off;
-  off = align_up(off + p->stream_items.size() * sizeof(DkItem), 256);
+  off = align_up(off + p->stream_items.size() * sizeof(DkItem), 16);
   p->off_links = off;
-  off = align_up(off + p->stream_links.size() * sizeof(int32_t), 256);
+  off = align_up(off + p->stream_links.size() * sizeof(int32_t), 16);
   p->off_merges = off;
-  off = align_up(off + p->merges.size() * sizeof(DkMerge), 256);
-  p->blob_bytes = off;
+  off = align_up(off + p->merges.size() * sizeof(DkMerge), 16);
+  p->blob_bytes = off;  // descriptors: small blobs travel in the kernel arguments, larger ones are uploaded
+  off = align_up(off, 256);
   p->off_parts = off;
   off += (size_t)p->part_rows * cfg.n_kv_heads * (cfg.head_dim + 2) * sizeof(float);
   p->total_bytes = align_up(off, 256) + 256;

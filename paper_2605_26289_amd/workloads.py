@@ -145,6 +145,30 @@ def config5(seed: int = BASE_SEED + 5, n_slots: int = 64, n_lo: int = 4096, n_hi
     return Workload("c5_spec_verify", PRODUCTION, n_slots, seed, history=[int(x) for x in n], turns=[turn])
 
 
+def mixed_prefill_decode(chunk: int, seed: int = BASE_SEED + 6, n_prefill: int = 4, n_decode: int = 60,
+                         prefill_n: int = 8192, n_lo: int = 4096, n_hi: int = 16384, k_draft: int = 8) -> Workload:
+    """Heterogeneous PREFILL+DECODE batch of one scheduler iteration (Sec. 3.2): n_prefill slots each take one prefill
+    chunk of `chunk` tokens (the caller sizes it with the chunking rule) on top of about prefill_n cached tokens, while
+    n_decode slots decode one token or verify a k_draft-token draft (Delta 1 or 1 + k_draft), all in one call, in a
+    seeded order.  Appended mode: the step appends every slot's new tokens, then attends."""
+    rng = np.random.default_rng(seed)
+    n_slots = n_prefill + n_decode
+    n_past = [int(prefill_n + rng.integers(0, 512)) for _ in range(n_prefill)]
+    n_past += rng.integers(n_lo, n_hi + 1, size=n_decode).tolist()
+    delta = [int(chunk)] * n_prefill + [int(1 + k_draft * int(rng.random() < 0.5)) for _ in range(n_decode)]
+    order = rng.permutation(n_slots).tolist()
+    turn = Turn([int(s) for s in order], [int(n_past[s]) for s in order], [int(delta[s]) for s in order])
+    return Workload("mixed_prefill_decode", PRODUCTION, n_slots, seed, history=[int(x) for x in n_past], turns=[turn])
+
+
+def token_stream(w: Workload, vocab: int = 50000) -> List[int]:
+    """Token ids of a single-conversation workload (configs 2 and 3), for the radix-cached per-turn procedure: the
+    prompt of turn t is the first n_past + delta ids."""
+    rng = np.random.default_rng(w.seed + 500)
+    total = (w.history[0] if w.history else 0) + sum(t.delta[0] for t in w.turns)
+    return rng.integers(0, vocab, size=total).tolist()
+
+
 def scaled(w: Workload, factor: float, min_tokens: int = 1) -> Workload:
     """Same structure with every length multiplied by `factor` (for cases the oracle finishes in seconds)."""
     f = lambda x: max(min_tokens, int(round(x * factor)))  # noqa: E731

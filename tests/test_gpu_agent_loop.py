@@ -151,3 +151,82 @@ def test_alg2_speculative_step_lookup_verify_accept_append():
         want = np.concatenate([acts[s][1][:-deltas[s]], kn[cu[s]:cu[s] + keep[s]]])
         assert np.array_equal(kg.float().cpu().numpy(), want)              # same contents as append-all-then-trim
     pool.close()
+
+
+def test_mixed_prefill_and_decode_batch_sized_by_the_chunking_rule():
+    """One scheduler iteration of Sec. 3.2: four slots prefill at once, so the chunking rule cuts the token batch
+    into equal chunks, and those chunks share ONE delta_attend call with decode (Delta = 1) and draft-verification
+    (Delta = 1 + k) rows of other slots -- the tile kernel and the streaming kernel both run inside the call.  At 1/8
+    of the lengths so that the oracle covers every row; production head shape."""
+    from gpu_util import Mirror
+    sh = wl.PRODUCTION
+    chunk = dk.prefill_chunk(4096 // 8, 4)                       # 512-token batch over 4 prefilling slots: 128 each
+    assert chunk == 128
+    w = wl.mixed_prefill_decode(chunk, n_prefill=4, n_decode=20, prefill_n=1024, n_lo=512, n_hi=2048)
+    t = w.turns[0]
+    assert sorted(set(t.delta)) == [1, 9, 128]                   # decode, verify and prefill rows in one batch
+    m = Mirror(sh, w.n_slots, w.cells_needed() + 256 * (w.n_slots + 2), seed=w.seed)
+    slots = [m.acquire() for _ in range(w.n_slots)]
+    for s, h in zip(slots, w.history):
+        m.append([s], [h])
+    q = m.draw(sum(t.delta), sh.n_q_heads)
+    m.append(t.slots, t.delta)
+    out, lse, _ = m.attend_appended(t.slots, t.delta, q, lse=True)
+    ref, ref_lse = m.oracle_appended(t.slots, t.delta, q)
+    check_close(out, ref, "bf16", "mixed prefill + decode batch")
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    m.pool.close()
+
+
+def test_alg2_step_with_nothing_read_back_between_its_stages():
+    """Alg. 2 as the benchmark times it: append all k+1 tokens, verify attention in appended mode, on-device argmax
+    and accept, asynchronous copy of the kept counts, and only then -- the deferred part -- one batched trim.  The
+    cache must end up exactly as after appending only the accepted tokens."""
+    from gpu_util import Mirror
+    sh = SH
+    rng = np.random.default_rng(10)
+    vocab, n_slots, k = 2048, 5, 8
+    m = Mirror(sh, n_slots, 1 << 14, seed=10)
+    slots = [m.acquire() for _ in range(n_slots)]
+    hist = [300, 1000, 37, 640, 2000]
+    for s, h in zip(slots, hist):
+        m.append([s], [h])
+    deltas = [1 + k] * n_slots
+    cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int32)
+    rows = int(cu[-1])
+    q = m.draw(rows, sh.n_q_heads)
+    kn, vn = m.draw(rows, sh.n_kv_heads), m.draw(rows, sh.n_kv_heads)
+    logits = wl.normal(rng, (rows, vocab), "bf16")
+    toks = rng.integers(0, vocab, size=rows).astype(np.int32)
+    agree = [8, 0, 3, 5, 1]
+    for s in range(n_slots):
+        for j in range(k):
+            want = int(toks[cu[s] + 1 + j]) if j < agree[s] else (int(toks[cu[s] + 1 + j]) + 1) % vocab
+            logits[cu[s] + j, want] = 60.0
+    keep_ref, _next_ref, _ = oracle.verify_batch(logits, toks, cu)
+    assert keep_ref.tolist() == [1 + a for a in agree]
+    # device side, one stream, no readback until the end
+    knd, vnd = to_dev(kn, "bf16"), to_dev(vn, "bf16")
+    m.pool.append(slots, cu, knd, vnd)
+    out = m.pool.attend(slots, cu, to_dev(q, "bf16"), sh.scale)
+    keep_d = torch.empty(n_slots, dtype=torch.int32, device="cuda")
+    next_d = torch.empty(n_slots, dtype=torch.int32, device="cuda")
+    ws = torch.empty(dk.verify_workspace_bytes(rows, vocab, dk.BF16), dtype=torch.uint8, device="cuda")
+    dk.verify_greedy(n_slots, rows, torch.from_numpy(cu).cuda(), to_dev(logits, "bf16"), dk.BF16, vocab, vocab,
+                     torch.from_numpy(toks).cuda(), keep_d, next_d, ws)
+    keep_h = torch.empty(n_slots, dtype=torch.int32, pin_memory=True)
+    keep_h.copy_(keep_d, non_blocking=True)
+    done = torch.cuda.Event()
+    done.record()
+    done.synchronize()                                            # the deferred part starts here
+    keep = keep_h.numpy()
+    assert np.array_equal(keep, keep_ref)
+    m.pool.trim_batch(slots, [h + int(c) for h, c in zip(hist, keep)])
+    # the oracle pool appends only the accepted tokens
+    for b, s in enumerate(slots):
+        m.model.append(s, kn[cu[b]:cu[b] + keep[b]], vn[cu[b]:cu[b] + keep[b]])
+        m.check_gather(s)
+    caches = [(m.cache(s)[0][:h], m.cache(s)[1][:h]) for s, h in zip(slots, hist)]
+    ref, _ = oracle.delta_attend_batch(q, caches, kn, vn, cu.astype(np.int64), sh.scale)
+    check_close(out, ref, "bf16", "verify attention over appended drafts")
+    m.pool.close()

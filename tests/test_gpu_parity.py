@@ -99,6 +99,14 @@ def test_config4_scaled_multi_agent_alias(variant):
     _run_turns(wl.scaled(wl.config4(), 0.125), granule=64, variant=variant)
 
 
+def test_scaled_configs_keep_the_production_head_shape():
+    """Configs 3-5 are checked on every row at 1/8 of their lengths but with the production heads (32 query heads on
+    8 KV heads), so the tile kernel's "workgroup id mod 8 = KV head" mapping, the levelled chains and the merge are
+    covered row by row, not on a sample."""
+    for w in (wl.scaled(wl.config3(), 0.125), wl.scaled(wl.config4(), 0.125), wl.scaled(wl.config5(n_slots=16), 0.125)):
+        assert (w.shape.n_q_heads, w.shape.n_kv_heads, w.shape.head_dim) == (32, 8, 128)
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_config5_scaled_spec_verify(variant):
     _run_turns(wl.scaled(wl.config5(n_slots=16), 0.125), variant=variant)
@@ -388,7 +396,7 @@ def test_random_batches_match_the_oracle(seed):
     staged or appended mode, two consecutive turns.  Whatever the planner makes of them -- row tiles, key chunks,
     merge records, chains of streaming units -- every output row must match the oracle."""
     rng = np.random.default_rng(9000 + seed)
-    sh = SMALL if seed % 3 else wl.Shape(16, 4, 128, "bf16")
+    sh = (wl.Shape(16, 4, 128, "bf16"), SMALL, wl.PRODUCTION)[seed % 3]
     n_slots = int(rng.integers(1, 13))
     granule = int(rng.choice([16, 64, 256]))
     hist = [int(rng.choice([0, rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 9000)])) for _ in range(n_slots)]
