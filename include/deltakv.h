@@ -328,6 +328,7 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
  *   stream_item_cost  fixed cost of a streaming unit in the chain balance, in keys  [0, 2^20]      default 512
  *   tile_wave_slots   tile-kernel workgroups of one KV head that run at a time      [1, 65536]     default 256 / Hkv
  *   tile_min_chunk    smallest key range worth its own tile item                    [64, 2^24]     default 128
+ *   tile_item_cost    fixed cost of a tile item inside a chain, in 64-key tiles     [0, 65536]     default 5
  *   xcd_speed0 .. xcd_speed7  relative K/V streaming rate of each XCD               (0, 100]       default 1
  * Affects only how later calls cut and order their work, never their results' meaning.
  */

@@ -25,6 +25,16 @@
 namespace dk {
 namespace mfma {
 
+#ifdef DK_TRACE  // timeline build: wall-clock stamps (100 MHz) per workgroup and unit
+__device__ unsigned long long g_strace[256][8][12];
+#define DK_STR(seq, ph)                                                                                      \
+  do {                                                                                                       \
+    if (lane == 0 && (seq) < 8 && blockIdx.x < 256) g_strace[blockIdx.x][(seq)][(ph)] = wall_clock64();       \
+  } while (0)
+#else
+#define DK_STR(seq, ph)
+#endif
+
 template <int MB>
 struct RowState {
   f32x16 o[4][MB];  // O^T accumulators: [depth block][row block], unnormalised
@@ -172,10 +182,16 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   // The workgroup walks its chain of units (item, KV head); the planner balanced the chains against
   // each other.
-  for (int unit = load_desc(links, blockIdx.x); unit >= 0;) {
+  int trace_seq = 0;
+  (void)trace_seq;
+  if (wave == 0) DK_STR(0, 10);
+  // The descriptors of a unit are fetched while the unit before it is being streamed, so that a unit change
+  // does not start with a chain of dependent memory round trips.
+  int unit = load_desc(links, blockIdx.x);
+  DkItem it = load_desc(c.items, unit / c.n_kv_heads);
+  DkEntry e = load_desc(c.entries, it.entry);
+  while (unit >= 0) {
   const int g = unit % c.n_kv_heads;
-  const DkItem it = load_desc(c.items, unit / c.n_kv_heads);
-  const DkEntry e = load_desc(c.entries, it.entry);
   const int last_row = it.row0 + it.nrows - 1;
   const int min_limit = e.n + (it.row0 >> c.gshift);
 
@@ -218,7 +234,17 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   bool have1 = have0 && cur.next(c, g, STREAM_KT, t1);
   if (have0) issue(t0, 0);
   if (have1) issue(t1, 1);
+  // (after this unit's own requests are out: the waits for these scalar loads fall into the wait for Q)
+  const int next_unit = load_desc(links, n_chains + unit);
+  DkItem next_it = it;
+  DkEntry next_e = e;
+  if (next_unit >= 0) {
+    next_it = load_desc(c.items, next_unit / c.n_kv_heads);
+    next_e = load_desc(c.entries, next_it.entry);
+  }
+  if (wave == 0) DK_STR(trace_seq, 0);
   wait_q<MB>(qf);
+  if (wave == 0) DK_STR(trace_seq, 1);
   int stage = 0;
   TileFrags fr;
   while (have0) {
@@ -240,8 +266,10 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
     stage ^= 1;
   }
 
+  DK_STR(trace_seq, 2 + wave);  // each wavefront's own end of streaming
   // ---- merge the four wavefront states -------------------------------------------------------
   __syncthreads();  // every wavefront is done with its stages: the space becomes the merge buffer
+  if (wave == 0) DK_STR(trace_seq, 6);
   float* obuf = (float*)smem;                       // [wave][db][mb][r][lane]
   float* ml = (float*)(smem + STREAM_ML_OFFSET);    // [wave][row 0..63][m, l]
 #pragma unroll
@@ -289,7 +317,14 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   }
   store_block<MB>(c, e, it, g, 0, lane, db, acc, ll);
   if (wave == 0) store_ml<MB>(c, e, it, g, 0, lane, mm, ll);
-  unit = load_desc(links, n_chains + unit);
+  if (wave == 0) DK_STR(trace_seq, 7);
+#ifdef DK_TRACE
+  if (threadIdx.x == 0 && trace_seq < 8 && blockIdx.x < 256) g_strace[blockIdx.x][trace_seq][8] = (unsigned long long)(it.kv_hi - it.kv_lo);
+  ++trace_seq;
+#endif
+  unit = next_unit;
+  it = next_it;
+  e = next_e;
   if (unit >= 0) __syncthreads();  // the merge buffer has been read everywhere: it may become K/V stages again
   }
 }
