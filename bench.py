@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c5",
-                    choices=["c5", "c4", "c4_512", "c3", "c2", "mixed", "c2_alg1", "c3_alg1", "alg2"])
+                    choices=["c5", "c4", "c4_512", "c3", "c2", "mixed", "c2_alg1", "c3_alg1", "alg2", "verify"])
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="planner tuning passed to dk_set_tuning on every pool (repeatable)")
     ap.add_argument("--host-profile", action="store_true",
@@ -639,6 +639,9 @@ def main():
         return
     if args.workload == "alg2":
         print(json.dumps(alg2_leg(wl.config5(k_draft=args.drafts), args.vocab, args.steps, args.warmup)))
+        return
+    if args.workload == "verify":
+        print(json.dumps(verify_leg(wl.config5(k_draft=args.drafts), args.vocab, args.steps, args.warmup)))
         return
     w, turn = make_workload(args.workload, args.drafts)
     keep = 0 if args.no_cpu_baseline else min(w.n_slots, 32)
