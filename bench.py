@@ -203,24 +203,32 @@ def make_workload(name, drafts=8):
 
 
 TUNING = []  # (name, value) pairs applied to every pool (--tune)
-TRAFFIC_SOURCE = "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command, kept in profiles/hbm_traffic.txt " \
-                 "with the commit they were taken at (not re-measured in this run)"
-
-
-def measured_traffic(name):
-    """HBM bytes per launch of the workload's dominant kernel as read by rocprofv3 counters (None if never profiled).
-
-    The counters cannot be read from inside this process; the readings of the profiled runs of this same command
-    are kept as text under profiles/ and quoted here."""
+def _traffic_table():
+    """Lines of profiles/hbm_traffic.txt: (commit the readings were taken at, {workload: bytes per launch})."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    commit, table = None, {}
     try:
         for line in open(path):
             f = line.split()
-            if len(f) == 4 and f[0] == name:
-                return int(f[2]) + int(f[3])
+            if len(f) == 3 and f[0] == "#" and f[1] == "commit":
+                commit = f[2]
+            elif len(f) == 4 and not line.startswith("#"):
+                table[f[0]] = table.get(f[0], 0) + int(f[2]) + int(f[3])
     except OSError:
         pass
-    return None
+    return commit, table
+
+
+TRAFFIC_COMMIT, _TRAFFIC = _traffic_table()
+TRAFFIC_SOURCE = "quoted: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of this command taken at commit " \
+                 f"{TRAFFIC_COMMIT}, kept in profiles/hbm_traffic.txt (all kernels of the call; not re-measured in this run)"
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of the workload's attention (or verification) kernels as read by rocprofv3 counters
+    (None if never profiled).  The counters cannot be read from inside this process; the readings of the profiled
+    runs of this same command are kept as text under profiles/ and quoted here."""
+    return _TRAFFIC.get(name)
 
 
 def roofline_for(name, flops, nbytes, kernel_ms):
