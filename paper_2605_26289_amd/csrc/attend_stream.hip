@@ -153,17 +153,57 @@ __device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&
 }
 
 // Accumulator r of depth block db is depth db*32 + 8*(r/4) + 4h + r%4: four consecutive depths per r/4.
-// Writes depth block `db` of the wavefront's rows, either as fp32 partial sums or as final bf16 output.
 // ------------------------------------------------------------------------------------------------
-// Stream kernel.  grid = items * n_kv_heads, block = 256.  Each wavefront owns a quarter of the item's
-// key range and two private 32-key stages (K 8 KiB + V 8 KiB each); no barrier in the loop.  At the
-// end the four (O, m, l) states are merged through LDS, wavefront w finishing depth block w.
+// Stream kernel.  grid = chains, block = 256.  A workgroup walks a chain of units (item, KV head).  Each
+// wavefront owns a quarter of the unit's key range and two private 32-key stages (K 8 KiB + V 8 KiB
+// each); no barrier in the key loop.  At the end of a unit the four (O, m, l) states are merged through
+// LDS, wavefront w finishing depth block w.
+//
+// Unit changes.  The merge buffer is the wavefronts' second stages only, one row block at a time, so that a
+// wavefront that has finished its quarter can at once request the next unit's first K/V tile into its first
+// stage; the next unit's Q rows are requested into an LDS area of their own right after the first merge
+// barrier (no wavefront reads the current Q any more then), and the second tile as soon as the merge buffer
+// has been read.  The merge thus runs under the latency of those requests instead of in front of it.
+//
+// LDS map: [0, 128 KiB) stages, wavefront w at w * 32 KiB (stage 0, stage 1); then the (m, l) exchange
+// (2 KiB); then the Q rows of the unit, laid out and swizzled like a K tile of MB * 32 rows.
 // ------------------------------------------------------------------------------------------------
 constexpr int STREAM_KT = 32;
 constexpr int STREAM_STAGE_BYTES = 2 * STREAM_KT * ROW_BYTES;  // 16 KiB
 constexpr int STREAM_WAVE_BYTES = 2 * STREAM_STAGE_BYTES;      // 32 KiB
-constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages / the merge buffer
-constexpr int STREAM_LDS_BYTES = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
+constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages
+constexpr int STREAM_Q_OFFSET = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
+constexpr int STREAM_LDS_BYTES = STREAM_Q_OFFSET + 2 * 32 * ROW_BYTES;
+
+// One wavefront moves 4 query rows (1 KiB) HBM -> LDS into the Q area: packed row `blk * 4 + l / 16` of the
+// unit (clamped to its last row), chunk slots swizzled as for a K tile so that read_k_frag serves as the
+// reader of Q's B-operand fragments.  Every wavefront requests all rows itself: each only depends on its own
+// requests, and the four write the same bytes.
+__device__ __forceinline__ void load_q_rows4(const Ctx& c, const char* q_tok0, int g, int row0, int last_row,
+                                             char* q_lds, int blk, int lane) {
+  const int row = blk * 4 + (lane >> 4);
+  const int slot = lane & 15;
+  const int chunk = slot ^ (row & 15);
+  const int arow = min(row0 + row, last_row);
+  const int gmask = (1 << c.gshift) - 1;
+  const uint32_t voff =
+      (uint32_t)(((arow >> c.gshift) * c.n_q_heads + (g << c.gshift) + (arow & gmask)) * ROW_BYTES + chunk * 16);
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)(q_lds + blk * 1024);
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, %2"
+      :
+      : "s"(lds_addr), "v"(voff), "s"(q_tok0)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ void lds_barrier() {
+  // LDS traffic of this wavefront has completed; K/V requests stay in flight (no vmcnt wait here)
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 // MB = 32-row blocks per unit: 1 when no unit of the launch has more than 32 packed rows (Delta <= 32 / G:
 // decode and short verify steps then skip the second, all-padding block), else 2.
@@ -180,48 +220,23 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   links = resolve_desc<INLINE>(links);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // The workgroup walks its chain of units (item, KV head); the planner balanced the chains against
-  // each other.
+  char* my = smem + wave * STREAM_WAVE_BYTES;
+  float* ml = (float*)(smem + STREAM_ML_OFFSET);  // [wave][row 0..63][m, l]
+  char* q_lds = smem + STREAM_Q_OFFSET;
+  const uint32_t koff = k_lane_off(lane);
   int trace_seq = 0;
   (void)trace_seq;
   if (wave == 0) DK_STR(0, 10);
-  // The descriptors of a unit are fetched while the unit before it is being streamed, so that a unit change
-  // does not start with a chain of dependent memory round trips.
+
+  // ---- the unit being streamed, and the requests that open a unit ----------------------------------
   int unit = load_desc(links, blockIdx.x);
   DkItem it = load_desc(c.items, unit / c.n_kv_heads);
   DkEntry e = load_desc(c.entries, it.entry);
-  while (unit >= 0) {
-  const int g = unit % c.n_kv_heads;
-  const int last_row = it.row0 + it.nrows - 1;
-  const int min_limit = e.n + (it.row0 >> c.gshift);
-
-  bf16x8 qf[MB][8];
-  int limit[MB];
-  load_q<MB>(c, e, g, it.row0, last_row, lane, qf, limit);
-
-  RowState<MB> st;
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    st.m[mb] = -INFINITY;
-    st.l[mb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.o[db][mb][r] = 0.f;
-  }
-
-  const int ntile = (it.kv_hi - it.kv_lo + STREAM_KT - 1) / STREAM_KT;
-  const int per = (ntile + 3) / 4 * STREAM_KT;
-  const int lo = min(it.kv_hi, it.kv_lo + wave * per);
-  const int hi = min(it.kv_hi, lo + per);
-  char* my = smem + wave * STREAM_WAVE_BYTES;
-
-  // Two private stages per wavefront.  A tile's fragments are read into registers as soon as it has
-  // landed and its stage is handed to the load of the tile after next at once, so two tiles (32 KiB per
-  // wavefront) are in flight while one is being computed -- with only the other stage loading, HBM
-  // latency would not be covered.
-  KvCursor cur{c.segs, e.seg_begin, e.seg_end, lo, hi};
+  int g = unit % c.n_kv_heads;
+  KvCursor cur{c.segs, 0, 0, 0, 0};
   KvTile t0, t1, t2;  // being computed, next, the one after
+  bool have0 = false, have1 = false;
+
   auto issue = [&](const KvTile& t, int stage) {
     char* kl = my + stage * STREAM_STAGE_BYTES;
     char* vl = kl + STREAM_KT * ROW_BYTES;
@@ -230,102 +245,162 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
 #pragma unroll
     for (int b = 0; b < 8; ++b) load_rows4<true>(t.v, t.stride, t.cnt, vl, b, lane);
   };
-  bool have0 = cur.next(c, g, STREAM_KT, t0);
-  bool have1 = have0 && cur.next(c, g, STREAM_KT, t1);
-  if (have0) issue(t0, 0);
-  if (have1) issue(t1, 1);
-  // (after this unit's own requests are out: the waits for these scalar loads fall into the wait for Q)
-  const int next_unit = load_desc(links, n_chains + unit);
-  DkItem next_it = it;
-  DkEntry next_e = e;
-  if (next_unit >= 0) {
-    next_it = load_desc(c.items, next_unit / c.n_kv_heads);
-    next_e = load_desc(c.entries, next_it.entry);
-  }
-  if (wave == 0) DK_STR(trace_seq, 0);
-  wait_q<MB>(qf);
-  if (wave == 0) DK_STR(trace_seq, 1);
-  int stage = 0;
-  TileFrags fr;
-  while (have0) {
-    if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
-    const char* kl = my + stage * STREAM_STAGE_BYTES;
-    read_frags(kl, kl + STREAM_KT * ROW_BYTES, lane, fr);
-    const bool have2 = have1 && cur.next(c, g, STREAM_KT, t2);
-    if (have2) {
-      // the stage may only be overwritten once every fragment read has returned
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      issue(t2, stage);
-    }
-    const bool need_mask = t0.cnt < STREAM_KT || t0.pos + STREAM_KT - 1 > min_limit;
-    compute_tile<MB>(fr, qf, st, limit, c.c, lane, t0.cnt, t0.pos, need_mask);
-    t0 = t1;
-    t1 = t2;
-    have0 = have1;
-    have1 = have2;
-    stage ^= 1;
-  }
-
-  DK_STR(trace_seq, 2 + wave);  // each wavefront's own end of streaming
-  // ---- merge the four wavefront states -------------------------------------------------------
-  __syncthreads();  // every wavefront is done with its stages: the space becomes the merge buffer
-  if (wave == 0) DK_STR(trace_seq, 6);
-  float* obuf = (float*)smem;                       // [wave][db][mb][r][lane]
-  float* ml = (float*)(smem + STREAM_ML_OFFSET);    // [wave][row 0..63][m, l]
+  // this wavefront's quarter of the unit's keys: cursor, first tile requested into stage 0
+  auto open_keys = [&](const DkItem& u, const DkEntry& ue, int ug) {
+    const int ntile = (u.kv_hi - u.kv_lo + STREAM_KT - 1) / STREAM_KT;
+    const int per = (ntile + 3) / 4 * STREAM_KT;
+    const int lo = min(u.kv_hi, u.kv_lo + wave * per);
+    const int hi = min(u.kv_hi, lo + per);
+    cur = KvCursor{c.segs, ue.seg_begin, ue.seg_end, lo, hi};
+    have0 = cur.next(c, ug, STREAM_KT, t0);
+    if (have0) issue(t0, 0);
+  };
+  auto open_q = [&](const DkItem& u, const DkEntry& ue, int ug) {
+    const char* q_tok0 = (const char*)c.q + (int64_t)ue.tok0 * c.n_q_heads * ROW_BYTES;
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
+    for (int b = 0; b < MB * 8; ++b) load_q_rows4(c, q_tok0, ug, u.row0, u.row0 + u.nrows - 1, q_lds, b, lane);
+  };
+  auto open_second = [&](int ug) {
+    have1 = have0 && cur.next(c, ug, STREAM_KT, t1);
+    if (have1) issue(t1, 1);
+  };
+
+  open_keys(it, e, g);
+  open_q(it, e, g);
+  open_second(g);
+
+  while (true) {
+    // The descriptors of the next unit are fetched while this one is being streamed, so that a unit change
+    // does not start with a chain of dependent memory round trips.
+    const int next_unit = load_desc(links, n_chains + unit);
+    DkItem next_it = it;
+    DkEntry next_e = e;
+    if (next_unit >= 0) {
+      next_it = load_desc(c.items, next_unit / c.n_kv_heads);
+      next_e = load_desc(c.entries, next_it.entry);
+    }
+    const int last_row = it.row0 + it.nrows - 1;
+    const int min_limit = e.n + (it.row0 >> c.gshift);
+
+    RowState<MB> st;
+    int limit[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      st.m[mb] = -INFINITY;
+      st.l[mb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[db][mb][r] = 0.f;
+      limit[mb] = e.n + (min(it.row0 + mb * 32 + (lane & 31), last_row) >> c.gshift);
+    }
+
+    // Everything requested before the second tile has arrived: the unit's Q rows and its first tile.
+    if (wave == 0) DK_STR(trace_seq, 0);
+    if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
+    bf16x8 qf[MB][8];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) obuf[(((wave * 4 + db) * MB + mb) * 16 + r) * 64 + lane] = st.o[db][mb][r];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    const float lt = st.l[mb] + __shfl_xor(st.l[mb], 32);
-    if (lane < 32) {
-      ml[(wave * 64 + mb * 32 + lane) * 2] = st.m[mb];
-      ml[(wave * 64 + mb * 32 + lane) * 2 + 1] = lt;
+      for (int ks = 0; ks < 8; ++ks) qf[mb][ks] = read_k_frag(q_lds, koff, mb, ks);
+    if (wave == 0) DK_STR(trace_seq, 1);
+
+    // Two private stages per wavefront.  A tile's fragments are read into registers as soon as it has
+    // landed and its stage is handed to the load of the tile after next at once, so two tiles (32 KiB per
+    // wavefront) are in flight while one is being computed -- with only the other stage loading, HBM
+    // latency would not be covered.
+    int stage = 0;
+    TileFrags fr;
+    while (have0) {
+      if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
+      const char* kl = my + stage * STREAM_STAGE_BYTES;
+      read_frags(kl, kl + STREAM_KT * ROW_BYTES, lane, fr);
+      const bool have2 = have1 && cur.next(c, g, STREAM_KT, t2);
+      if (have2) {
+        // the stage may only be overwritten once every fragment read has returned
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        issue(t2, stage);
+      }
+      const bool need_mask = t0.cnt < STREAM_KT || t0.pos + STREAM_KT - 1 > min_limit;
+      compute_tile<MB>(fr, qf, st, limit, c.c, lane, t0.cnt, t0.pos, need_mask);
+      t0 = t1;
+      t1 = t2;
+      have0 = have1;
+      have1 = have2;
+      stage ^= 1;
     }
-  }
-  __syncthreads();
-  const int db = wave;
-  f32x16 acc[MB];
-  float mm[MB], ll[MB];
+    DK_STR(trace_seq, 2 + wave);  // each wavefront's own end of streaming
+
+    // ---- unit change: both stages of this wavefront are free ----------------------------------------
+    const int next_g = next_unit % c.n_kv_heads;
+    if (next_unit >= 0) open_keys(next_it, next_e, next_g);  // (have0, t0, cur now belong to the next unit)
+
+    // ---- merge the four wavefront states ------------------------------------------------------------
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    const int row = mb * 32 + (lane & 31);
-    float mw[4], lw[4];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      mw[w] = ml[(w * 64 + row) * 2];
-      lw[w] = ml[(w * 64 + row) * 2 + 1];
-      mx = fmaxf(mx, mw[w]);
+    for (int mb = 0; mb < MB; ++mb) {
+      const float lt = st.l[mb] + __shfl_xor(st.l[mb], 32);
+      if (lane < 32) {
+        ml[(wave * 64 + mb * 32 + lane) * 2] = st.m[mb];
+        ml[(wave * 64 + mb * 32 + lane) * 2 + 1] = lt;
+      }
     }
-    const float ms = (mx == -INFINITY) ? 0.f : mx;
-    float lsum = 0.f;
+    const int db = wave;
+    f32x16 acc[MB];
+    float mm[MB], ll[MB];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+    for (int mb = 0; mb < MB; ++mb) {
+      // row block mb of every wavefront's O goes through the wavefronts' second stages: [db][r][lane]
+      float* mine = (float*)(my + STREAM_STAGE_BYTES);
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = __builtin_amdgcn_exp2f(mw[w] - ms);
-      lsum += f * lw[w];
+      for (int d4 = 0; d4 < 4; ++d4)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mb][r] += f * obuf[(((w * 4 + db) * MB + mb) * 16 + r) * 64 + lane];
+        for (int r = 0; r < 16; ++r) mine[(d4 * 16 + r) * 64 + lane] = st.o[d4][mb][r];
+      lds_barrier();
+      if (mb == 0) {
+        if (wave == 0) DK_STR(trace_seq, 6);
+        // no wavefront reads the current unit's Q any more: the next unit's may land
+        if (next_unit >= 0) open_q(next_it, next_e, next_g);
+      }
+      const int row = mb * 32 + (lane & 31);
+      float mw[4], lw[4];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        mw[w] = ml[(w * 64 + row) * 2];
+        lw[w] = ml[(w * 64 + row) * 2 + 1];
+        mx = fmaxf(mx, mw[w]);
+      }
+      const float ms = (mx == -INFINITY) ? 0.f : mx;
+      float lsum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float f = __builtin_amdgcn_exp2f(mw[w] - ms);
+        lsum += f * lw[w];
+        const float* theirs = (const float*)(smem + w * STREAM_WAVE_BYTES + STREAM_STAGE_BYTES);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] += f * theirs[(db * 16 + r) * 64 + lane];
+      }
+      mm[mb] = mx;
+      ll[mb] = lsum;
+      // the buffer has been read everywhere: the next row block, or the next unit's second tile, may overwrite it
+      if (mb + 1 < MB || next_unit >= 0) lds_barrier();
     }
-    mm[mb] = mx;
-    ll[mb] = lsum;
-  }
-  store_block<MB>(c, e, it, g, 0, lane, db, acc, ll);
-  if (wave == 0) store_ml<MB>(c, e, it, g, 0, lane, mm, ll);
-  if (wave == 0) DK_STR(trace_seq, 7);
+    store_block<MB>(c, e, it, g, 0, lane, db, acc, ll);
+    if (wave == 0) store_ml<MB>(c, e, it, g, 0, lane, mm, ll);
+    // (after the stores: the wait that opens the next unit lets exactly this request stay in flight)
+    if (next_unit >= 0) open_second(next_g);
+    if (wave == 0) DK_STR(trace_seq, 7);
 #ifdef DK_TRACE
-  if (threadIdx.x == 0 && trace_seq < 8 && blockIdx.x < 256) g_strace[blockIdx.x][trace_seq][8] = (unsigned long long)(it.kv_hi - it.kv_lo);
-  ++trace_seq;
+    if (threadIdx.x == 0 && trace_seq < 8 && blockIdx.x < 256) g_strace[blockIdx.x][trace_seq][8] = (unsigned long long)(it.kv_hi - it.kv_lo);
+    ++trace_seq;
 #endif
-  unit = next_unit;
-  it = next_it;
-  e = next_e;
-  if (unit >= 0) __syncthreads();  // the merge buffer has been read everywhere: it may become K/V stages again
+    if (next_unit < 0) break;
+    unit = next_unit;
+    it = next_it;
+    e = next_e;
+    g = next_g;
   }
 }
 
