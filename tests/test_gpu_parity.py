@@ -389,6 +389,33 @@ def test_many_small_slots_walk_chains_of_units(n_slots, n_hi):
     m.pool.close()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_chains_of_streaming_units_with_one_and_two_row_blocks(seed):
+    """Hundreds of slots with Delta from 0 up to the streaming kernel's limit (64 packed rows: both its one-block
+    and its two-block form), short and long histories, two turns: every workgroup changes units many times, each
+    change overlapping the next unit's first requests with the merge of the finished one."""
+    rng = np.random.default_rng(77000 + seed)
+    sh = (SMALL, wl.PRODUCTION, wl.Shape(16, 4, 128, "bf16"))[seed % 3]
+    group = sh.n_q_heads // sh.n_kv_heads
+    n_slots = min(int(rng.integers(40, 700)), 250 if sh is wl.PRODUCTION else 700)
+    n_hi = int(rng.choice([30, 90, 400, 1500]))
+    m = Mirror(sh, n_slots, n_slots * (n_hi + 40) + 4096, granule=int(rng.choice([16, 64])), seed=seed)
+    slots = [m.acquire() for _ in range(n_slots)]
+    hist = rng.integers(0, n_hi + 1, size=n_slots).tolist()
+    m.append([s for s, h in zip(slots, hist) if h], [h for h in hist if h])
+    for turn in range(2):
+        deltas = rng.integers(0, 64 // group + 1, size=n_slots).tolist()
+        if turn == 1:
+            deltas = [min(d, 32 // group) for d in deltas]  # one row block everywhere
+        q = m.draw(sum(deltas), sh.n_q_heads)
+        m.append(slots, deltas)
+        out, lse, _ = m.attend_appended(slots, deltas, q, lse=True)
+        ref, ref_lse = m.oracle_appended(slots, deltas, q)
+        check_close(out, ref, sh.dtype, f"seed {seed} turn {turn}", row_scaled=True)
+        assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    m.pool.close()
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_random_batches_match_the_oracle(seed):
     """Seeded random batch structures: slot count, histories (some grown over several appends and trimmed back,
