@@ -41,6 +41,9 @@ def parse():
                     choices=["c5", "c4", "c4_512", "c3", "c2", "mixed", "c2_alg1", "c3_alg1", "alg2", "verify"])
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="planner tuning passed to dk_set_tuning on every pool (repeatable)")
+    ap.add_argument("--step", default="fused", choices=["fused", "separate"],
+                    help="fused: dk_append_attend (one launch appends and attends) then the trims; separate: "
+                         "dk_kv_append and dk_delta_attend as two calls, in the order the workload's mode states")
     ap.add_argument("--host-profile", action="store_true",
                     help="instead of the benchmark, print where the host time of a step goes (plan, upload, launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,8 +117,11 @@ class Scenario:
         self.v_new = torch.randn((total, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(dt)
         self.out = torch.empty_like(self.q)
         self.n_accept = np.asarray(t.n_accept, dtype=np.int32) if t.staged and t.n_accept else None
+        self.keep_len = None if self.n_accept is None else t.n_past + self.n_accept.astype(np.int64)
         # size the workspace once, in the state the attend call will see
-        if t.staged:
+        if FUSED_STEP:
+            self.pool.ensure_workspace(t.slots, self.cu, 2)
+        elif t.staged:
             self.pool.ensure_workspace(t.slots, self.cu, True)
         else:
             self.pool.append(t.slots, self.cu, self.k_new, self.v_new)
@@ -142,7 +148,13 @@ class Scenario:
 
     def step(self):
         t = self.turn
-        if t.staged:
+        if FUSED_STEP:
+            # Decode(sigma, batch): all new tokens appended and attended by one launch; a verification batch then
+            # drops its rejected drafts (Alg. 2's trim), host metadata only
+            self.pool.append_attend(t.slots, self.cu, self.q, self.k_new, self.v_new, self.sh.scale, out=self.out)
+            if self.keep_len is not None:
+                self.pool.trim_batch(t.slots, self.keep_len)
+        elif t.staged:
             self.pool.attend(t.slots, self.cu, self.q, self.sh.scale, self.k_new, self.v_new, out=self.out)
             self.pool.append(t.slots, self.cu, self.k_new, self.v_new, self.n_accept)
         else:
@@ -210,6 +222,7 @@ def make_workload(name, drafts=8):
 
 
 TUNING = []  # (name, value) pairs applied to every pool (--tune)
+FUSED_STEP = True  # --step: dk_append_attend per step; False: dk_kv_append and dk_delta_attend as separate calls
 def _traffic_table():
     """Lines of profiles/hbm_traffic.txt: (commit the readings were taken at, {workload: bytes per launch})."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
@@ -342,8 +355,11 @@ def alg1_leg(w, reps, warmup):
             past.append(n_past)
             d = n - n_past
             cu = np.asarray([0, d], dtype=np.int32)
-            pool.append([slot], cu, k[:d], v[:d])
-            pool.attend([slot], cu, q[:d], sh.scale, out=out[:d])
+            if FUSED_STEP:
+                pool.append_attend([slot], cu, q[:d], k[:d], v[:d], sh.scale, out=out[:d])
+            else:
+                pool.append([slot], cu, k[:d], v[:d])
+                pool.attend([slot], cu, q[:d], sh.scale, out=out[:d])
             if record and t == n_turns - 1:
                 seg, depth = dk.seq_stats(pool.handle, slot)
                 layout.update(segments_last_turn=seg, alias_generations=depth)
@@ -429,6 +445,7 @@ def alg2_leg(w, vocab, steps, warmup):
     vws = torch.empty(dk.verify_workspace_bytes(rows, vocab, dk.BF16), dtype=torch.uint8, device="cuda")
     copied = torch.cuda.Event()
     slots_sorted = slots[np.asarray(t.slots)]
+    pool.ensure_workspace(slots_sorted, cu, 2)
     pool.append(slots_sorted, cu, kn, vn)
     pool.ensure_workspace(slots_sorted, cu, False)
     pool.trim_batch(slots_sorted, n_past)
@@ -444,8 +461,11 @@ def alg2_leg(w, vocab, steps, warmup):
 
     def step():
         settle()
-        pool.append(slots_sorted, cu, kn, vn)
-        pool.attend(slots_sorted, cu, q, sh.scale, out=out)
+        if FUSED_STEP:
+            pool.append_attend(slots_sorted, cu, q, kn, vn, sh.scale, out=out)
+        else:
+            pool.append(slots_sorted, cu, kn, vn)
+            pool.attend(slots_sorted, cu, q, sh.scale, out=out)
         dk.verify_greedy(n, rows, cu_d, logits, dk.BF16, vocab, vocab, toks, keep_d, next_d, vws)
         keep_h.copy_(keep_d, non_blocking=True)
         copied.record()
@@ -586,11 +606,17 @@ def host_profile(args):
     torch.cuda.synchronize()
     n = max(args.steps, 200)
     dk.host_times(sc.pool.handle, reset=True)
-    acc = {"kv_append": [], "delta_attend": [], "trim_batch": []}
+    acc = {"append_attend": [], "kv_append": [], "delta_attend": [], "trim_batch": []}
     t_all = time.perf_counter()
     for _ in range(n):
         a = time.perf_counter()
-        if t.staged:
+        if FUSED_STEP:
+            sc.pool.append_attend(t.slots, sc.cu, sc.q, sc.k_new, sc.v_new, sc.sh.scale, out=sc.out)
+            c = time.perf_counter()
+            acc["append_attend"].append(c - a)
+            if sc.keep_len is not None:
+                sc.pool.trim_batch(t.slots, sc.keep_len)
+        elif t.staged:
             sc.pool.attend(t.slots, sc.cu, sc.q, sc.sh.scale, sc.k_new, sc.v_new, out=sc.out)
             b = time.perf_counter()
             sc.pool.append(t.slots, sc.cu, sc.k_new, sc.v_new, sc.n_accept)
@@ -606,6 +632,7 @@ def host_profile(args):
             acc["delta_attend"].append(c - b)
         sc._rewind()
         acc["trim_batch"].append(time.perf_counter() - c)
+    acc = {k: v for k, v in acc.items() if v}
     host_wall = time.perf_counter() - t_all
     torch.cuda.synchronize()
     total_wall = time.perf_counter() - t_all
@@ -642,6 +669,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_per_launch": n, "launches": 5}))
         return
+    global FUSED_STEP
+    FUSED_STEP = args.step == "fused"
     for item in args.tune:
         name, _, value = item.partition("=")
         TUNING.append((name, float(value)))
@@ -670,8 +699,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": sc.sh.dtype, "data": "synthetic",
         "config": {"workload": w.name, "slots": w.n_slots, "new_tokens_per_step": int(sc.total),
                    "n_q_heads": sc.sh.n_q_heads, "n_kv_heads": sc.sh.n_kv_heads, "head_dim": sc.sh.head_dim,
-                   "cached_tokens": int(sum(sc.turn.n_past)), "mode": "staged" if sc.turn.staged else "appended",
-                   "step": "delta_attend + kv_append + trim"},
+                   "cached_tokens": int(sum(sc.turn.n_past)), "mode": "fused" if FUSED_STEP else ("staged" if sc.turn.staged else "appended"),
+                   "step": ("append_attend + trim" if FUSED_STEP else
+                            "delta_attend + kv_append + trim" if sc.turn.staged else "kv_append + delta_attend + trim")},
         "ms_per_step_no_events": round(sc.ms_per_step_no_events, 4),
         "attend_kernel_ms": round(kern_med_ms, 4), "attend_kernel_ms_mean": round(kern_mean_ms, 4),
         "attend_only_tokens_per_s": round(sc.total / (kern_med_ms * 1e-3), 1),

@@ -179,6 +179,7 @@ int32_t dk_kv_reserve(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const
  *          scaled scores of each row
  *   workspace  DEVICE, 256-byte aligned, at least dk_attend_workspace_bytes() for the same
  *          (slots, cu_delta, mode) and the same slot lengths; DK_ERR_WORKSPACE otherwise
+ *          (dk_attend_workspace_bytes: staged = 0 appended mode, 1 staged mode, 2 dk_append_attend)
  * Entries with Delta_b == 0 produce no rows; n_b == 0 is legal.
  */
 int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
@@ -186,6 +187,22 @@ int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* 
 int32_t dk_delta_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
                         const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
                         int64_t workspace_bytes, void* stream);
+
+/*
+ * append_attend: Decode(sigma, batch) of paper Alg. 1 as one call -- appends all Delta_b new tokens of every entry
+ * to its slot and attends them (row i of entry b over the slot's n_b = len tokens before the call plus new tokens
+ * 0..i).  The final pool state and the results are those of dk_kv_append (n_accept NULL) followed by
+ * dk_delta_attend in appended mode; the K/V rows are written into the arena by the attention kernels themselves, so
+ * no separate copy kernel runs.  A speculative step (Alg. 2) appends its k+1 rows this way and drops the rejected
+ * ones afterwards with dk_seq_trim / dk_seq_trim_batch.
+ *   k_new, v_new  DEVICE, required (layout as in dk_kv_append); the other arguments as in dk_delta_attend
+ *   workspace     at least dk_attend_workspace_bytes(..., staged = 2, ...) for the same batch and slot lengths
+ * Errors as for the two calls it replaces (DK_ERR_NO_CELLS: nothing appended, nothing launched); a failing call
+ * leaves the lengths unchanged.
+ */
+int32_t dk_append_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                         const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                         int64_t workspace_bytes, void* stream);
 
 /*
  * delta_attend for callers that cannot allocate and have no workspace to hand over: code under HIP graph

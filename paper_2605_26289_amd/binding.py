@@ -59,6 +59,8 @@ SIGNATURES = {
     "dk_attend_workspace_bytes": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_int32, _I64P]),
     "dk_delta_attend": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
+    "dk_append_attend": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "dk_delta_attend_noalloc": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
@@ -242,7 +244,8 @@ def kv_reserve(pool, slots, cu_delta, n_accept=None) -> np.ndarray:
     return out
 
 
-def attend_workspace_bytes(pool, slots, cu_delta, staged: bool) -> int:
+def attend_workspace_bytes(pool, slots, cu_delta, staged) -> int:
+    """staged: False / 0 appended mode, True / 1 staged mode, 2 for append_attend."""
     s_arr, s_p = _i32(slots)
     c_arr, c_p = _i32(cu_delta)
     out = C.c_int64()
@@ -260,6 +263,17 @@ def delta_attend(pool, slots, cu_delta, q, out, scale: float, k_new=None, v_new=
     _launch(lambda: lib().dk_delta_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new),
                                           float(scale), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, st),
             "delta_attend", pool, stream)
+
+
+def append_attend(pool, slots, cu_delta, q, k_new, v_new, out, scale: float, lse=None, workspace=None,
+                  stream=None) -> None:
+    s_arr, s_p = _i32(slots)
+    c_arr, c_p = _i32(cu_delta)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = _stream(stream)
+    _launch(lambda: lib().dk_append_attend(pool, len(s_arr), s_p, c_p, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                           float(scale), _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, st),
+            "append_attend", pool, stream)
 
 
 STATIC_SCRATCH_BYTES = 32 << 20

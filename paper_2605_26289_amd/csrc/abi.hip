@@ -74,9 +74,11 @@ struct dk_pool {
   int64_t host_calls[2] = {0, 0};  // dk_delta_attend*, dk_kv_append
   std::mutex launch_mu;  // serialises GPU-launching calls (shared staging ring, dev_meta and plan)
   dk::AttendPlan plan;   // reused from call to call so that steady-state planning allocates nothing
+  std::vector<int64_t> append_cells, append_old_len;  // likewise, for the bookkeeping of appends
 
   dk_pool(const dk_pool_desc& d, int32_t granule)
-      : desc(d), meta(d.n_slots, d.n_session_slots, d.arena_cells, granule) {}
+      : desc(d), meta(d.n_slots, d.n_session_slots, d.arena_cells, granule), granule_cells(granule) {}
+  int32_t granule_cells;
 
   dk::ArenaView view() const {
     return {desc.k_arena, desc.v_arena, meta_arena_cells, desc.n_q_heads, desc.n_kv_heads, desc.head_dim, desc.dtype};
@@ -282,51 +284,70 @@ int32_t dk_pool_stats(dk_pool* pool, int64_t* held, int64_t* free_cells) {
   return pool ? pool->meta.stats(held, free_cells) : DK_ERR_INVALID;
 }
 
+}  // extern "C"
+
+namespace {
+
+void undo_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const std::vector<int64_t>& old_len) {
+  for (int32_t b = 0; b < n_seqs; ++b) (void)pool->meta.trim(slots[b], old_len[b]);
+}
+
+// dk_kv_append with pool->launch_mu held.  Leaves the slots' previous lengths in pool->append_old_len.
+int32_t append_locked(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                      const int32_t* n_accept, const void* k_new, const void* v_new, void* stream) {
+  PhaseClock clk;
+  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+  if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
+  const bool inline_cells = total <= dk::KV_INLINE_MAX_TOKENS;
+  const int64_t per_launch =
+      std::min<int64_t>(pool->desc.dev_meta_bytes, (int64_t)pool->stage_cap) / (int64_t)sizeof(int32_t);
+  if (!inline_cells && per_launch <= 0) return DK_ERR_WORKSPACE;  // long appends need staging memory
+  std::vector<int64_t>& dst = pool->append_cells;
+  std::vector<int64_t>& old_len = pool->append_old_len;
+  int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst, &old_len);
+  if (rc != DK_OK) return rc;
+  // From here on a failure must leave the pool as it was: the bookkeeping is rolled back.
+  const auto undo = [&](int32_t status) {
+    undo_append(pool, n_seqs, slots, old_len);
+    return status;
+  };
+  hipStream_t st = (hipStream_t)stream;
+  pool->host_us[DK_HOST_APPEND_BOOK] += clk.lap();
+  ++pool->host_calls[1];
+  if (inline_cells) {
+    hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
+                                                (int32_t)total, k_new, v_new, st);
+    pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
+    return e == hipSuccess ? DK_OK : undo(pool->hip_fail(e));
+  }
+  for (int64_t base = 0; base < total; base += per_launch) {
+    const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);
+    Staging* s;
+    rc = pool->stage((size_t)n * sizeof(int32_t), &s);
+    // Chunks already enqueued wrote cells that the rolled-back slots no longer own: harmless, they are free.
+    if (rc != DK_OK) return undo(rc);
+    int32_t* h = (int32_t*)s->host;
+    for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)dst[base + t];
+    rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
+    if (rc != DK_OK) return undo(rc);
+    hipError_t e = dk::launch_kv_scatter(pool->view(), pool->desc.k_arena, pool->desc.v_arena,
+                                         (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
+    if (e != hipSuccess) return undo(pool->hip_fail(e));
+  }
+  pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
+  return DK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int32_t dk_kv_append(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
                      const int32_t* n_accept, const void* k_new, const void* v_new, void* stream) {
   if (!pool) return DK_ERR_INVALID;
   return guarded([&]() -> int32_t {
     std::lock_guard<std::mutex> launch(pool->launch_mu);
-    PhaseClock clk;
-    const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
-    if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
-    const bool inline_cells = total <= dk::KV_INLINE_MAX_TOKENS;
-    const int64_t per_launch =
-        std::min<int64_t>(pool->desc.dev_meta_bytes, (int64_t)pool->stage_cap) / (int64_t)sizeof(int32_t);
-    if (!inline_cells && per_launch <= 0) return DK_ERR_WORKSPACE;  // long appends need staging memory
-    std::vector<int64_t> dst, old_len;
-    int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, n_accept, &dst, &old_len);
-    if (rc != DK_OK) return rc;
-    // From here on a failure must leave the pool as it was: the bookkeeping is rolled back.
-    const auto undo = [&](int32_t status) {
-      for (int32_t b = 0; b < n_seqs; ++b) (void)pool->meta.trim(slots[b], old_len[b]);
-      return status;
-    };
-    hipStream_t st = (hipStream_t)stream;
-    pool->host_us[DK_HOST_APPEND_BOOK] += clk.lap();
-    ++pool->host_calls[1];
-    if (inline_cells) {
-      hipError_t e = dk::launch_kv_scatter_inline(pool->view(), pool->desc.k_arena, pool->desc.v_arena, dst.data(),
-                                                  (int32_t)total, k_new, v_new, st);
-      pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
-      return e == hipSuccess ? DK_OK : undo(pool->hip_fail(e));
-    }
-    for (int64_t base = 0; base < total; base += per_launch) {
-      const int32_t n = (int32_t)std::min<int64_t>(per_launch, total - base);
-      Staging* s;
-      rc = pool->stage((size_t)n * sizeof(int32_t), &s);
-      // Chunks already enqueued wrote cells that the rolled-back slots no longer own: harmless, they are free.
-      if (rc != DK_OK) return undo(rc);
-      int32_t* h = (int32_t*)s->host;
-      for (int32_t t = 0; t < n; ++t) h[t] = (int32_t)dst[base + t];
-      rc = pool->upload(s, pool->desc.dev_meta, (size_t)n * sizeof(int32_t), st);
-      if (rc != DK_OK) return undo(rc);
-      hipError_t e = dk::launch_kv_scatter(pool->view(), pool->desc.k_arena, pool->desc.v_arena,
-                                           (const int32_t*)pool->desc.dev_meta, base, n, k_new, v_new, st);
-      if (e != hipSuccess) return undo(pool->hip_fail(e));
-    }
-    pool->host_us[DK_HOST_APPEND_LAUNCH] += clk.lap();
-    return DK_OK;
+    return append_locked(pool, n_seqs, slots, cu_delta, n_accept, k_new, v_new, stream);
   });
 }
 
@@ -385,22 +406,38 @@ int32_t dk_attend_workspace_bytes(dk_pool* pool, int32_t n_seqs, const int32_t* 
     dk::PlanConfig cfg = pool->cfg;
     if (pool->variant == 1) cfg.use_mfma = false;
     std::lock_guard<std::mutex> lk(pool->meta.mutex());
-    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged != 0, &plan);
+    if (staged < 0 || staged > 2) return DK_ERR_INVALID;
+    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged != 0, &plan, staged == 2);
     if (rc != DK_OK) return rc;
     *bytes_out = (int64_t)plan.total_bytes;
+    // dk_append_attend may also plan the batch after its append, in appended mode: the same work items over slots
+    // that then have more runs of cells (at worst one per granule the append takes)
+    if (staged == 2)
+      *bytes_out += ((int64_t)n_seqs * 8 + plan.total_tokens / pool->granule_cells + 16) * (int64_t)sizeof(DkSeg) + 4096;
     return DK_OK;
   });
 }
 
 namespace {
 
-// Plans the call, uploads its descriptors into `workspace` and launches the attention kernels.
-int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
-                    const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
-                    int64_t workspace_bytes, void* stream) {
+// A private status of attend_locked: the call is not one whose append can be folded into the attention kernel.
+constexpr int32_t kNotFoldable = 1;
+// Calls above these sizes are not even planned for folding (their descriptors cannot fit the kernel arguments).
+constexpr int32_t kFoldMaxSeqs = 16;
+constexpr int64_t kFoldMaxTokens = 384;
+
+// Plans the call, uploads its descriptors into `workspace` and launches the attention kernels.  pool->launch_mu
+// is held.
+// fold_append: the call also appends all new tokens to their slots, provided that its descriptors fit the kernel
+// arguments and an MFMA kernel runs (otherwise kNotFoldable is returned and nothing has happened): the attention is
+// planned on the slots as they are (staged mode), the bookkeeping follows, and the rows are written into the arena
+// by the attention kernel itself.
+int32_t attend_locked(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                      const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                      int64_t workspace_bytes, void* stream, bool fold_append) {
   if ((k_new == nullptr) != (v_new == nullptr)) return DK_ERR_INVALID;
-  std::lock_guard<std::mutex> launch(pool->launch_mu);
   const bool staged = k_new != nullptr;
+  if (fold_append && !staged) return DK_ERR_INVALID;
   PhaseClock clk;
   dk::AttendPlan& plan = pool->plan;
   dk::PlanConfig cfg = pool->cfg;
@@ -408,24 +445,38 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   if (pool->variant == 1 || !(scale > 0.f) || !(scale < 3.0e38f)) cfg.use_mfma = false;
   {
     std::lock_guard<std::mutex> lk(pool->meta.mutex());
-    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged, &plan);
+    int32_t rc = dk::build_plan(pool->meta, cfg, n_seqs, slots, cu_delta, staged, &plan, fold_append);
     if (rc != DK_OK) return rc;
   }
   if (plan.total_tokens == 0) return DK_OK;
   if (!q || !out) return DK_ERR_INVALID;
+  const bool inline_blob = plan.blob_bytes <= (size_t)dk::INLINE_BLOB_BYTES;
+  if (fold_append && !(inline_blob && cfg.use_mfma && (plan.tile_chains > 0 || plan.stream_chains > 0)))
+    return kNotFoldable;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)plan.total_bytes) return DK_ERR_WORKSPACE;
+  // The bookkeeping half of a folded append.  From here on a failure must leave the pool as it was.
+  std::vector<int64_t>& dst = pool->append_cells;
+  std::vector<int64_t>& old_len = pool->append_old_len;
+  if (fold_append) {
+    const int32_t rc = pool->meta.append(n_seqs, slots, cu_delta, nullptr, &dst, &old_len);
+    if (rc != DK_OK) return rc;
+    ++pool->host_calls[1];
+  }
+  const auto fail = [&](int32_t status) {
+    if (fold_append) undo_append(pool, n_seqs, slots, old_len);
+    return status;
+  };
   pool->host_us[DK_HOST_PLAN] += clk.lap();
 
   hipStream_t st = (hipStream_t)stream;
   // Small descriptor blobs travel inside the kernel arguments; larger ones go through a staging buffer into
   // the workspace.
-  const bool inline_blob = plan.blob_bytes <= (size_t)dk::INLINE_BLOB_BYTES;
   dk::InlineBlob blob_args{};
   char* h = (char*)&blob_args;
   Staging* s = nullptr;
   if (!inline_blob) {
     const int32_t rc = pool->stage(plan.blob_bytes, &s);
-    if (rc != DK_OK) return rc;
+    if (rc != DK_OK) return fail(rc);
     h = s->host;
   }
   auto put = [&](size_t off, const void* src, size_t bytes) { if (bytes) std::memcpy(h + off, src, bytes); };
@@ -436,10 +487,14 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
   put(plan.off_links, plan.stream_links.data(), plan.stream_links.size() * sizeof(int32_t));
   put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
+  if (fold_append) {
+    int32_t* cells = (int32_t*)(h + plan.off_cells);
+    for (int64_t t = 0; t < plan.total_tokens; ++t) cells[t] = (int32_t)dst[t];
+  }
   pool->host_us[DK_HOST_STAGE] += clk.lap();
   if (!inline_blob) {
     const int32_t rc = pool->upload(s, workspace, plan.blob_bytes, st);
-    if (rc != DK_OK) return rc;
+    if (rc != DK_OK) return fail(rc);
   }
   pool->host_us[DK_HOST_UPLOAD] += clk.lap();
 
@@ -461,39 +516,77 @@ int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const i
   a.parts_ml = a.parts + (size_t)plan.part_rows * pool->desc.n_kv_heads * pool->desc.head_dim;
   a.scale = scale;
   a.total_tokens = (int32_t)plan.total_tokens;
+  a.cells = (const int32_t*)(desc + plan.off_cells);
 
   hipError_t e = hipSuccess;
   const bool timing = !pool->ev0.empty();
   const size_t ev_slot = timing ? (size_t)(pool->ev_calls % (int64_t)pool->ev0.size()) : 0;
   if (timing) {
     e = hipEventRecord(pool->ev0[ev_slot], st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
   }
   if (!cfg.use_mfma) {
     e = dk::launch_attend_ref(a, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
   } else {
+    // a folded append is carried out by the first MFMA kernel of the call
+    a.scatter = fold_append && plan.tile_chains > 0;
     e = dk::launch_attend_tile(a, (const DkItem*)(desc + plan.off_tile), (const int32_t*)(desc + plan.off_tile_links),
                                plan.tile_chains, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
+    a.scatter = fold_append && plan.tile_chains == 0;
     int32_t stream_rows = 0;
     for (const DkItem& it : plan.stream_items) stream_rows = std::max(stream_rows, it.nrows);
     e = dk::launch_attend_stream(a, (const DkItem*)(desc + plan.off_stream), (const int32_t*)(desc + plan.off_links),
                                  plan.stream_chains, stream_rows, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
+    a.scatter = false;
     int32_t max_rows = 0;
     for (const DkMerge& mg : plan.merges) max_rows = std::max(max_rows, mg.nrows);
     e = dk::launch_attend_merge(a, (const DkMerge*)(desc + plan.off_merges), (int32_t)plan.merges.size(), max_rows, st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
   }
   if (timing) {  // the interval covers every kernel of the call, the merge of split key ranges included
     e = hipEventRecord(pool->ev1[ev_slot], st);
-    if (e != hipSuccess) return pool->hip_fail(e);
+    if (e != hipSuccess) return fail(pool->hip_fail(e));
     ++pool->ev_calls;
   }
   pool->host_us[DK_HOST_LAUNCH] += clk.lap();
   ++pool->host_calls[0];
   return DK_OK;
+}
+
+int32_t attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                    const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                    int64_t workspace_bytes, void* stream) {
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  return attend_locked(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, workspace, workspace_bytes,
+                       stream, false);
+}
+
+// dk_append_attend.  A small call (its descriptors and cell table fit the kernel arguments) is one launch: the
+// attention kernel writes the new rows itself.  Any other call is what dk_kv_append followed by dk_delta_attend in
+// appended mode would be (measured: for large batches the copy inside the attention kernel costs about what the
+// separate copy kernel does, and attending the new rows from the arena beats reading them token-major).
+int32_t append_attend_impl(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
+                           const void* q, const void* k_new, const void* v_new, float scale, void* out, float* lse,
+                           void* workspace, int64_t workspace_bytes, void* stream) {
+  std::lock_guard<std::mutex> launch(pool->launch_mu);
+  const int64_t total = (n_seqs > 0 && cu_delta) ? cu_delta[n_seqs] : 0;
+  if (total > 0 && (!k_new || !v_new)) return DK_ERR_INVALID;
+  if (n_seqs <= kFoldMaxSeqs && total <= kFoldMaxTokens) {
+    const int32_t rc = attend_locked(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, workspace,
+                                     workspace_bytes, stream, true);
+    if (rc != kNotFoldable) return rc;
+  }
+  if (total > 0 && (!q || !out)) return DK_ERR_INVALID;
+  int32_t rc = append_locked(pool, n_seqs, slots, cu_delta, nullptr, k_new, v_new, stream);
+  if (rc != DK_OK) return rc;
+  rc = attend_locked(pool, n_seqs, slots, cu_delta, q, nullptr, nullptr, scale, out, lse, workspace, workspace_bytes,
+                     stream, false);
+  // (the copy kernel already enqueued wrote cells that the rolled-back slots no longer own: harmless, they are free)
+  if (rc != DK_OK) undo_append(pool, n_seqs, slots, pool->append_old_len);
+  return rc;
 }
 
 }  // namespace
@@ -540,6 +633,16 @@ int32_t dk_delta_attend_noalloc(dk_pool* pool, int32_t n_seqs, const int32_t* sl
     // a call that needs more than the array holds is turned down by the size check (DK_ERR_WORKSPACE)
     return attend_impl(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, ws,
                        (int64_t)DK_STATIC_SCRATCH_BYTES, stream);
+  });
+}
+
+int32_t dk_append_attend(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta, const void* q,
+                         const void* k_new, const void* v_new, float scale, void* out, float* lse, void* workspace,
+                         int64_t workspace_bytes, void* stream) {
+  if (!pool) return DK_ERR_INVALID;
+  return guarded([&]() -> int32_t {
+    return append_attend_impl(pool, n_seqs, slots, cu_delta, q, k_new, v_new, scale, out, lse, workspace,
+                              workspace_bytes, stream);
   });
 }
 

@@ -68,6 +68,8 @@ struct Ctx {
   float c;  // softmax scale * log2(e): scores are handled in log2 units
   int32_t n_q_heads, n_kv_heads, gshift;
   int64_t arena_cells;
+  const int32_t* cells;  // small append-and-attend calls: arena cell of every new token
+  int32_t n_scatter;     // how many tokens this launch writes into the arena (0: none)
 };
 
 // A run of at most KT consecutive K/V rows, all inside one segment.
@@ -339,6 +341,46 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Append-and-attend calls small enough for their descriptors to travel in the kernel arguments: the attention
+// kernel also writes the call's new K/V rows (token-major, as staged in k_new / v_new) into their arena cells, so
+// that no separate copy kernel has to be launched.  The cells are fresh ones that no attention work of this launch
+// reads (the new tokens are attended from the staged rows), so the order against the rest of the kernel is free:
+// every workgroup copies an equal run right after its first K/V requests, whose latency covers the copy's.
+// The copy is cut into 16-byte pieces, piece p = (token, K or V, KV head, position in the row); a thread has four
+// loads in flight before its first store.
+template <bool INLINE>
+__device__ __forceinline__ void scatter_new_rows(const Ctx& c) {
+  if (c.n_scatter <= 0) return;
+  const int32_t* cells = resolve_desc<INLINE>(c.cells);
+  const int vecs = c.n_kv_heads * (ROW_BYTES / 16);  // pieces of one token's K (as many for V)
+  const int total = c.n_scatter * 2 * vecs;
+  const int per = ((total + (int)gridDim.x - 1) / (int)gridDim.x + 255) & ~255;
+  const int begin = min(total, (int)blockIdx.x * per), end = min(total, begin + per);
+  const auto locate = [&](int p, const char*& src, char*& dst) {
+    p = min(p, end - 1);  // (threads past the end repeat the last piece: same bytes)
+    const int t = p / (2 * vecs), r = p - t * (2 * vecs);
+    const bool is_v = r >= vecs;
+    const int j = is_v ? r - vecs : r;
+    const int g = j / (ROW_BYTES / 16), piece = j % (ROW_BYTES / 16);
+    const int64_t cell = cells[t];
+    src = (is_v ? c.v_new : c.k_new) + ((int64_t)t * c.n_kv_heads + g) * ROW_BYTES + piece * 16;
+    dst = const_cast<char*>(is_v ? c.v_arena : c.k_arena) + ((int64_t)g * c.arena_cells + cell) * ROW_BYTES + piece * 16;
+  };
+  for (int base = begin + (int)threadIdx.x; base < end; base += 4 * 256) {
+    const char *s0, *s1, *s2, *s3;
+    char *d0, *d1, *d2, *d3;
+    locate(base, s0, d0);
+    locate(base + 256, s1, d1);
+    locate(base + 512, s2, d2);
+    locate(base + 768, s3, d3);
+    const uint4 v0 = *(const uint4*)s0, v1 = *(const uint4*)s1, v2 = *(const uint4*)s2, v3 = *(const uint4*)s3;
+    *(uint4*)d0 = v0;
+    *(uint4*)d1 = v1;
+    *(uint4*)d2 = v2;
+    *(uint4*)d3 = v3;
+  }
+}
+
 inline Ctx make_ctx(const AttendArgs& a, const DkItem* items) {
   Ctx c;
   c.entries = a.entries;
@@ -360,6 +402,8 @@ inline Ctx make_ctx(const AttendArgs& a, const DkItem* items) {
   while ((1 << sh) < group) ++sh;
   c.gshift = sh;
   c.arena_cells = a.arena.arena_cells;
+  c.cells = a.cells;
+  c.n_scatter = a.scatter ? a.total_tokens : 0;
   return c;
 }
 

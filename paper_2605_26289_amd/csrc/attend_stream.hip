@@ -268,6 +268,9 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   open_keys(it, e, g);
   open_q(it, e, g);
   open_second(g);
+  // small append-and-attend calls: this workgroup's share of the new rows goes into the arena now, under the
+  // latency of the first unit's requests
+  scatter_new_rows<INLINE>(c);
 
   while (true) {
     // The descriptors of the next unit are fetched while this one is being streamed, so that a unit change

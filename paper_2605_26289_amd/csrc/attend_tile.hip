@@ -537,6 +537,9 @@ __global__ __launch_bounds__(256, 1) void attend_tile_kernel(BlobArg<INLINE> blo
     const DkItem first = load_desc(c.items, item_idx);
     begin_item(first, load_desc(c.entries, first.entry));
   }
+  // small append-and-attend calls: this workgroup's share of the new rows goes into the arena now, under the
+  // latency of the first item's requests
+  scatter_new_rows<INLINE>(c);
 
   while (true) {
     // the next item of the chain: its descriptors arrive while this one is being computed

@@ -53,6 +53,10 @@ struct AttendArgs {
   float* parts_ml;  // [partial row][KV head][2]: running maximum (log2 units), weight sum
   float scale;
   int32_t total_tokens;
+  // Small append-and-attend calls: destination arena cell of every new token (a section of the inline descriptor
+  // blob); the MFMA kernel launched with `scatter` set also writes the rows of k_new / v_new into those cells.
+  const int32_t* cells = nullptr;
+  bool scatter = false;
 };
 
 // Scalar reference kernel: one wavefront per (token, query head).  Any supported shape and dtype.

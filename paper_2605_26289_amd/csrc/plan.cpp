@@ -238,7 +238,7 @@ void cut_tile_items(AttendPlan* p, const PlanConfig& cfg) {
 }  // namespace
 
 int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
-                   bool staged, AttendPlan* p) {
+                   bool staged, AttendPlan* p, bool with_cells) {
   int32_t rc = pool.check_batch(n_seqs, slots, cu_delta);
   if (rc != OK) return rc;
   p->entries.clear();
@@ -309,6 +309,8 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
   off = align_up(off + p->stream_links.size() * sizeof(int32_t), 16);
   p->off_merges = off;
   off = align_up(off + p->merges.size() * sizeof(DkMerge), 16);
+  p->off_cells = off;
+  if (with_cells) off = align_up(off + (size_t)p->total_tokens * sizeof(int32_t), 16);
   p->blob_bytes = off;  // descriptors: small blobs travel in the kernel arguments, larger ones are uploaded
   off = align_up(off, 256);
   p->off_parts = off;

@@ -65,13 +65,15 @@ struct AttendPlan {
   std::vector<int32_t> tile_links;
   int32_t tile_chains = 0;
   size_t off_entries = 0, off_segs = 0, off_tile = 0, off_tile_links = 0, off_stream = 0, off_links = 0, off_merges = 0;
+  size_t off_cells = 0;    // destination cell of every new token (int32), only when the plan was built with_cells
   size_t blob_bytes = 0;   // descriptors
   size_t off_parts = 0;    // fp32 partial rows, each (head_dim + 2) floats per KV head
   size_t total_bytes = 0;  // whole workspace
 };
 
-// Caller holds pool.mutex().
+// Caller holds pool.mutex().  with_cells reserves, inside the descriptor blob, one int32 per new token for the
+// cell it is to be written to (the call that appends and attends in one launch fills them in).
 int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int32_t* slots, const int32_t* cu_delta,
-                   bool staged, AttendPlan* plan);
+                   bool staged, AttendPlan* plan, bool with_cells = false);
 
 }  // namespace dk

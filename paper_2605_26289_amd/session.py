@@ -89,7 +89,7 @@ class DevicePool:
     def append(self, slots: Sequence[int], cu_delta: Sequence[int], k_new, v_new, n_accept=None) -> None:
         dk.kv_append(self.handle, slots, cu_delta, k_new, v_new, n_accept)
 
-    def ensure_workspace(self, slots, cu_delta, staged: bool) -> torch.Tensor:
+    def ensure_workspace(self, slots, cu_delta, staged) -> torch.Tensor:
         need = dk.attend_workspace_bytes(self.handle, slots, cu_delta, staged)
         if self.workspace is None or self.workspace.numel() < need:
             self.workspace = torch.empty(int(need * 1.25) + 4096, dtype=torch.uint8, device=self.device)
@@ -107,6 +107,21 @@ class DevicePool:
                 raise
             ws = self.ensure_workspace(slots, cu_delta, k_new is not None)
             dk.delta_attend(self.handle, slots, cu_delta, q, out, scale, k_new, v_new, lse, ws)
+        return out
+
+    def append_attend(self, slots, cu_delta, q, k_new, v_new, scale: float, out=None, lse=None):
+        """Appends every entry's new tokens and attends them, in one call (no separate copy kernel)."""
+        if out is None:
+            out = torch.empty_like(q)
+        if self.workspace is None:
+            self.ensure_workspace(slots, cu_delta, 2)
+        try:
+            dk.append_attend(self.handle, slots, cu_delta, q, k_new, v_new, out, scale, lse, self.workspace)
+        except dk.DeltaKVError as e:
+            if e.name != "WORKSPACE":
+                raise
+            ws = self.ensure_workspace(slots, cu_delta, 2)
+            dk.append_attend(self.handle, slots, cu_delta, q, k_new, v_new, out, scale, lse, ws)
         return out
 
     def gather(self, slot: int):

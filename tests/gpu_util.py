@@ -115,6 +115,19 @@ class Mirror:
         out = self.pool.attend(slots, cu, qd, self.shape.scale, lse=lse_t)
         return out, lse_t, cu
 
+    def append_attend(self, slots, deltas, q, lse=False):
+        """dk_append_attend: draws the new K/V, appends and attends in one call; the host copy follows."""
+        cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int32)
+        k = self.draw(int(cu[-1]), self.shape.n_kv_heads)
+        v = self.draw(int(cu[-1]), self.shape.n_kv_heads)
+        qd = to_dev(q, self.shape.dtype)
+        lse_t = torch.empty((int(cu[-1]), self.shape.n_q_heads), dtype=torch.float32, device="cuda") if lse else None
+        out = self.pool.append_attend(slots, cu, qd, to_dev(k, self.shape.dtype), to_dev(v, self.shape.dtype),
+                                      self.shape.scale, lse=lse_t)
+        for b, s in enumerate(slots):
+            self.model.append(s, k[cu[b]:cu[b + 1]], v[cu[b]:cu[b + 1]])
+        return out, lse_t, cu
+
     def oracle_appended(self, slots, deltas, q, rows_per_seq=None):
         cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int64)
         hkv, d = self.shape.n_kv_heads, self.shape.head_dim

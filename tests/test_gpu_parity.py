@@ -389,6 +389,72 @@ def test_many_small_slots_walk_chains_of_units(n_slots, n_hi):
     m.pool.close()
 
 
+APPEND_ATTEND_CASES = {
+    # name: (shape, histories, deltas of two turns)
+    "tile": (wl.PRODUCTION, [900, 0, 3000], [[300, 70, 129], [64, 17, 700]]),
+    "stream": (wl.PRODUCTION, [5, 0, 2100, 333, 64], [[9, 1, 16, 0, 3], [1, 1, 9, 2, 0]]),
+    "mixed": (SMALL, [1200, 40, 0, 700], [[400, 1, 3, 16], [2, 260, 9, 0]]),
+    "fp32 reference path": (wl.Shape(4, 2, 64, "f32"), [200, 0, 31], [[150, 3, 1], [1, 40, 0]]),
+    "long single turn": (wl.PRODUCTION, [0], [[1500], [1100]]),
+    # small calls: the copy is folded into the tile kernel, the stream kernel, and the first of both
+    "small tile turn": (wl.PRODUCTION, [800], [[150], [150]]),
+    "small stream step": (wl.PRODUCTION, [700, 0, 64], [[9, 1, 4], [1, 9, 16]]),
+    "small tile and stream": (SMALL, [300, 20], [[40, 2], [3, 70]]),
+}
+
+
+@pytest.mark.parametrize("case", sorted(APPEND_ATTEND_CASES))
+def test_append_attend_is_append_then_attend(case):
+    """dk_append_attend against dk_kv_append + dk_delta_attend on a twin pool fed the same rows: results against the
+    oracle, then lengths, cell numbers and the gathered arena contents of every slot bit for bit."""
+    sh, hist, turns = APPEND_ATTEND_CASES[case]
+    cells = sum(hist) + sum(sum(t) for t in turns) + len(hist) * 600 + 1024
+    fused, plain = Mirror(sh, len(hist), cells, granule=64, seed=5), Mirror(sh, len(hist), cells, granule=64, seed=5)
+    slots = [fused.acquire() for _ in hist]
+    assert slots == [plain.acquire() for _ in hist]
+    for m in (fused, plain):
+        m.append([s for s, h in zip(slots, hist) if h], [h for h in hist if h])
+    for turn, deltas in enumerate(turns):
+        q = fused.draw(sum(deltas), sh.n_q_heads)
+        plain.draw(sum(deltas), sh.n_q_heads)  # keep the twin's generator in step
+        out_f, lse_f, _ = fused.append_attend(slots, deltas, q, lse=True)
+        plain.append(slots, deltas)
+        out_p, lse_p, _ = plain.attend_appended(slots, deltas, q, lse=True)
+        ref, ref_lse = fused.oracle_appended(slots, deltas, q)
+        check_close(out_f, ref, sh.dtype, f"{case} turn {turn} fused", row_scaled=True)
+        check_close(out_p, ref, sh.dtype, f"{case} turn {turn} plain", row_scaled=True)
+        assert np.abs(lse_f.cpu().numpy() - ref_lse).max() < 2e-3
+        for s in slots:
+            assert fused.pool.length(s) == plain.pool.length(s)
+            assert np.array_equal(dk.seq_cells(fused.pool.handle, s), dk.seq_cells(plain.pool.handle, s))
+            fused.check_gather(s)
+            kf, vf = fused.pool.gather(s)
+            kp, vp = plain.pool.gather(s)
+            assert torch.equal(kf, kp) and torch.equal(vf, vp)
+    fused.pool.close()
+    plain.pool.close()
+
+
+def test_append_attend_that_does_not_fit_changes_nothing():
+    sh = SMALL
+    m = Mirror(sh, 2, 512, granule=64, seed=1)
+    a, b = m.acquire(), m.acquire()
+    m.append([a, b], [100, 50])
+    deltas = [300, 200]  # 500 more cells than the arena has left
+    cu = np.concatenate([[0], np.cumsum(deltas)]).astype(np.int32)
+    q = to_dev(m.draw(sum(deltas), sh.n_q_heads), sh.dtype)
+    k = to_dev(m.draw(sum(deltas), sh.n_kv_heads), sh.dtype)
+    with pytest.raises(dk.DeltaKVError, match="NO_CELLS"):
+        m.pool.append_attend([a, b], cu, q, k, k, sh.scale)
+    assert (m.pool.length(a), m.pool.length(b)) == (100, 50)
+    m.check_gather(a)
+    m.check_gather(b)
+    with pytest.raises(dk.DeltaKVError, match="INVALID"):  # the new rows are required
+        dk.append_attend(m.pool.handle, [a], [0, 4], q, None, None, torch.empty_like(q), sh.scale, None,
+                         m.pool.ensure_workspace([a], [0, 4], 2))
+    m.pool.close()
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_chains_of_streaming_units_with_one_and_two_row_blocks(seed):
     """Hundreds of slots with Delta from 0 up to the streaming kernel's limit (64 packed rows: both its one-block
