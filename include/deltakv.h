@@ -9,7 +9,8 @@
  *   - every function returns an int32_t status (DK_OK == 0, errors negative), never
  *     throws, aborts or prints;
  *   - a call that fails leaves the pool's state unchanged;
- *   - calls that launch GPU work (dk_kv_append, dk_delta_attend, dk_seq_gather) are
+ *   - calls that launch GPU work (dk_kv_append, dk_delta_attend, dk_append_attend,
+ *     dk_delta_attend_noalloc, dk_seq_gather, dk_verify_greedy) are
  *     asynchronous on the HIP stream passed as `stream` (a hipStream_t cast to void*,
  *     NULL = the default stream).  They never wait for the device and never allocate
  *     device or pinned memory: descriptors travel through the caller's staging memory
