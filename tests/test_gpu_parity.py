@@ -523,6 +523,15 @@ def test_random_batches_match_the_oracle(seed):
             ref, _ = oracle.delta_attend_batch(q, [m.cache(s) for s in sl], kn, vn, cu, sh.scale)
             check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} staged", row_scaled=True)
             m.append(sl, dl, kn, vn, n_accept=[int(rng.integers(0, d + 1)) for d in dl])
+        elif (seed + turn) % 2:  # both at once: dk_append_attend
+            lse = torch.empty((total, sh.n_q_heads), dtype=torch.float32, device="cuda")
+            out = m.pool.append_attend(sl, cu, to_dev(q, sh.dtype), to_dev(kn, sh.dtype), to_dev(vn, sh.dtype),
+                                       sh.scale, lse=lse)
+            for b, s in enumerate(sl):
+                m.model.append(s, kn[cu[b]:cu[b + 1]], vn[cu[b]:cu[b + 1]])
+            ref, ref_lse = m.oracle_appended(sl, dl, q)
+            check_close(out, ref, sh.dtype, f"seed {seed} turn {turn} append_attend", row_scaled=True)
+            assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
         else:
             m.append(sl, dl, kn, vn)
             out, lse, _ = m.attend_appended(sl, dl, q, lse=True)
