@@ -216,6 +216,8 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
     c.stream_chains = 256;
     c.stream_item_cost = 512;
     for (float& x : c.xcd_speed) x = 1.f;
+    c.stream_queue = 1;
+    c.inline_blob_bytes = dk::INLINE_BLOB_BYTES;
     *pool_out = p;
     return DK_OK;
   });
@@ -244,6 +246,7 @@ int32_t dk_set_tuning(dk_pool* pool, const char* name, double value) {
   if (key == "stream_min_chunk") return whole(64, 1 << 24, &c.stream_min_chunk);
   if (key == "stream_chains") return whole(1, 1 << 16, &c.stream_chains);
   if (key == "stream_item_cost") return whole(0, 1 << 20, &c.stream_item_cost);
+  if (key == "stream_queue") return whole(0, 1, &c.stream_queue);
   if (key == "tile_wave_slots") return whole(1, 1 << 16, &c.tile_wave_slots);
   if (key == "tile_min_chunk") return whole(64, 1 << 24, &c.tile_min_chunk);
   if (key == "tile_item_cost") return whole(0, 1 << 16, &c.tile_item_cost);
@@ -450,7 +453,7 @@ int32_t attend_locked(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const
   }
   if (plan.total_tokens == 0) return DK_OK;
   if (!q || !out) return DK_ERR_INVALID;
-  const bool inline_blob = plan.blob_bytes <= (size_t)dk::INLINE_BLOB_BYTES;
+  const bool inline_blob = plan.blob_bytes <= (size_t)dk::INLINE_BLOB_BYTES && !plan.stream_queued;
   if (fold_append && !(inline_blob && cfg.use_mfma && (plan.tile_chains > 0 || plan.stream_chains > 0)))
     return kNotFoldable;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)plan.total_bytes) return DK_ERR_WORKSPACE;
@@ -487,6 +490,10 @@ int32_t attend_locked(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const
   put(plan.off_stream, plan.stream_items.data(), plan.stream_items.size() * sizeof(DkItem));
   put(plan.off_links, plan.stream_links.data(), plan.stream_links.size() * sizeof(int32_t));
   put(plan.off_merges, plan.merges.data(), plan.merges.size() * sizeof(DkMerge));
+  if (plan.stream_queued) {  // the queue's counter: the first stream_chains units are taken when the kernel starts
+    const int32_t first[4] = {plan.stream_chains, 0, 0, 0};
+    put(plan.off_queue, first, sizeof(first));
+  }
   if (fold_append) {
     int32_t* cells = (int32_t*)(h + plan.off_cells);
     for (int64_t t = 0; t < plan.total_tokens; ++t) cells[t] = (int32_t)dst[t];
@@ -538,7 +545,9 @@ int32_t attend_locked(dk_pool* pool, int32_t n_seqs, const int32_t* slots, const
     int32_t stream_rows = 0;
     for (const DkItem& it : plan.stream_items) stream_rows = std::max(stream_rows, it.nrows);
     e = dk::launch_attend_stream(a, (const DkItem*)(desc + plan.off_stream), (const int32_t*)(desc + plan.off_links),
-                                 plan.stream_chains, stream_rows, st);
+                                 plan.stream_chains, stream_rows,
+                                 plan.stream_queued ? (int32_t*)(ws + plan.off_queue) : nullptr,
+                                 (int32_t)plan.stream_units, st);
     if (e != hipSuccess) return fail(pool->hip_fail(e));
     a.scatter = false;
     int32_t max_rows = 0;

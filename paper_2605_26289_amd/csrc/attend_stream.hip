@@ -165,15 +165,27 @@ __device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&
 // barrier (no wavefront reads the current Q any more then), and the second tile as soon as the merge buffer
 // has been read.  The merge thus runs under the latency of those requests instead of in front of it.
 //
+// Which unit comes next.  Small launches (descriptors in the kernel arguments) walk the chains the planner linked.
+// Otherwise the units form one queue, longest first: workgroup w starts with unit w and every further unit is
+// drawn from a counter in device memory (uploaded with the descriptors, starting at the number of workgroups) by
+// one atomic add.  The compute units do not stream equally fast -- by 10 % and more between XCDs, differently from
+// box to box and batch to batch -- so chains of equal length planned on the host end up to 25 % apart; with the
+// queue a faster workgroup simply takes the next unit earlier.  Wavefront 0 draws half-way through its share of
+// the current unit (the order of drawing is the order of finishing, and the round trip is hidden), fetches the
+// drawn unit's descriptors and hands them to the other wavefronts through LDS at the unit's end.  Which workgroup
+// computes a unit has no influence on the unit's result.
+//
 // LDS map: [0, 128 KiB) stages, wavefront w at w * 32 KiB (stage 0, stage 1); then the (m, l) exchange
-// (2 KiB); then the Q rows of the unit, laid out and swizzled like a K tile of MB * 32 rows.
+// (2 KiB); then the Q rows of the unit, laid out and swizzled like a K tile of MB * 32 rows; then the next
+// unit's descriptors as published by wavefront 0.
 // ------------------------------------------------------------------------------------------------
 constexpr int STREAM_KT = 32;
 constexpr int STREAM_STAGE_BYTES = 2 * STREAM_KT * ROW_BYTES;  // 16 KiB
 constexpr int STREAM_WAVE_BYTES = 2 * STREAM_STAGE_BYTES;      // 32 KiB
 constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages
 constexpr int STREAM_Q_OFFSET = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
-constexpr int STREAM_LDS_BYTES = STREAM_Q_OFFSET + 2 * 32 * ROW_BYTES;
+constexpr int STREAM_NEXT_OFFSET = STREAM_Q_OFFSET + 2 * 32 * ROW_BYTES;
+constexpr int STREAM_LDS_BYTES = STREAM_NEXT_OFFSET + 128;
 
 // One wavefront moves 4 query rows (1 KiB) HBM -> LDS into the Q area: packed row `blk * 4 + l / 16` of the
 // unit (clamped to its last row), chunk slots swizzled as for a K tile so that read_k_frag serves as the
@@ -211,7 +223,7 @@ __device__ __forceinline__ void lds_barrier() {
 // offsets into them; otherwise they point into the uploaded workspace.
 template <int MB, bool INLINE>
 __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> blob, Ctx c, const int32_t* links,
-                                                               int n_chains) {
+                                                               int n_chains, int32_t* queue, int n_units) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   (void)blob;
   c.entries = resolve_desc<INLINE>(c.entries);
@@ -223,13 +235,14 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   char* my = smem + wave * STREAM_WAVE_BYTES;
   float* ml = (float*)(smem + STREAM_ML_OFFSET);  // [wave][row 0..63][m, l]
   char* q_lds = smem + STREAM_Q_OFFSET;
+  int32_t* next_lds = (int32_t*)(smem + STREAM_NEXT_OFFSET);  // [0] unit, [4..11] its DkItem, [12..19] its DkEntry
   const uint32_t koff = k_lane_off(lane);
+  const bool queued = !INLINE && queue != nullptr;  // units are drawn from the queue (else: the planner's chains)
   int trace_seq = 0;
   (void)trace_seq;
-  if (wave == 0) DK_STR(0, 10);
 
   // ---- the unit being streamed, and the requests that open a unit ----------------------------------
-  int unit = load_desc(links, blockIdx.x);
+  int unit = queued ? (int)blockIdx.x : load_desc(links, blockIdx.x);
   DkItem it = load_desc(c.items, unit / c.n_kv_heads);
   DkEntry e = load_desc(c.entries, it.entry);
   int g = unit % c.n_kv_heads;
@@ -268,6 +281,7 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   open_keys(it, e, g);
   open_q(it, e, g);
   open_second(g);
+  if (wave == 0) DK_STR(0, 10);  // (kernel entry, a few scalar loads late)
   // small append-and-attend calls: this workgroup's share of the new rows goes into the arena now, under the
   // latency of the first unit's requests
   scatter_new_rows<INLINE>(c);
@@ -275,13 +289,25 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   while (true) {
     // The descriptors of the next unit are fetched while this one is being streamed, so that a unit change
     // does not start with a chain of dependent memory round trips.
-    const int next_unit = load_desc(links, n_chains + unit);
+    int next_unit = -1;
     DkItem next_it = it;
     DkEntry next_e = e;
-    if (next_unit >= 0) {
-      next_it = load_desc(c.items, next_unit / c.n_kv_heads);
-      next_e = load_desc(c.entries, next_it.entry);
+    if (!queued) {
+      next_unit = load_desc(links, n_chains + unit);
+      if (next_unit >= 0) {
+        next_it = load_desc(c.items, next_unit / c.n_kv_heads);
+        next_e = load_desc(c.entries, next_it.entry);
+      }
     }
+    // queue: wavefront 0 draws in iteration draw_at of its key loop (an ordinary atomic: the compiler keeps account
+    // of it and waits for the answer where it is first used, after the loop, when no K/V request is in flight)
+    const bool drawer = queued && wave == 0;
+    int drawn = 0;
+    bool drew = false;
+    const auto draw = [&]() {
+      if (lane == 0) drawn = __hip_atomic_fetch_add(queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      drew = true;
+    };
     const int last_row = it.row0 + it.nrows - 1;
     const int min_limit = e.n + (it.row0 >> c.gshift);
 
@@ -314,11 +340,17 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
     // latency would not be covered.
     int stage = 0;
     TileFrags fr;
+    // (wavefront 0's share of the unit is at least this many tiles: ragged segment ends only add some)
+    const int my_tiles = ((it.kv_hi - it.kv_lo + STREAM_KT - 1) / STREAM_KT + 3) / 4;
+    const int draw_at = my_tiles / 2;
+    int iter = 0;
     while (have0) {
       if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
       const char* kl = my + stage * STREAM_STAGE_BYTES;
       read_frags(kl, kl + STREAM_KT * ROW_BYTES, lane, fr);
       const bool have2 = have1 && cur.next(c, g, STREAM_KT, t2);
+      if (drawer && !drew && iter >= draw_at) draw();
+      ++iter;
       if (have2) {
         // the stage may only be overwritten once every fragment read has returned
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -335,8 +367,29 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
     DK_STR(trace_seq, 2 + wave);  // each wavefront's own end of streaming
 
     // ---- unit change: both stages of this wavefront are free ----------------------------------------
-    const int next_g = next_unit % c.n_kv_heads;
-    if (next_unit >= 0) open_keys(next_it, next_e, next_g);  // (have0, t0, cur now belong to the next unit)
+    if (drawer) {
+      if (!drew) draw();  // (a share with no tiles at all)
+      const int q = __builtin_amdgcn_readfirstlane(drawn);
+      next_unit = q < n_units ? q : -1;
+      if (next_unit >= 0) {
+        next_it = load_desc(c.items, next_unit / c.n_kv_heads);
+        next_e = load_desc(c.entries, next_it.entry);
+      }
+      if (lane == 0) {
+        next_lds[0] = next_unit;
+        next_lds[4] = next_it.entry;
+        next_lds[5] = next_it.row0;
+        next_lds[6] = next_it.nrows;
+        next_lds[7] = next_it.kv_lo;
+        next_lds[8] = next_it.kv_hi;
+        next_lds[9] = next_it.part_row0;
+        next_lds[12] = next_e.seg_begin;
+        next_lds[13] = next_e.seg_end;
+        next_lds[14] = next_e.n;
+        next_lds[15] = next_e.delta;
+        next_lds[16] = next_e.tok0;
+      }
+    }
 
     // ---- merge the four wavefront states ------------------------------------------------------------
 #pragma unroll
@@ -347,6 +400,7 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
         ml[(wave * 64 + mb * 32 + lane) * 2 + 1] = lt;
       }
     }
+    int next_g = 0;
     const int db = wave;
     f32x16 acc[MB];
     float mm[MB], ll[MB];
@@ -361,8 +415,28 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
       lds_barrier();
       if (mb == 0) {
         if (wave == 0) DK_STR(trace_seq, 6);
-        // no wavefront reads the current unit's Q any more: the next unit's may land
-        if (next_unit >= 0) open_q(next_it, next_e, next_g);
+        if (queued) {  // what wavefront 0 drew (field by field: the values must stay in scalar registers)
+          const auto word = [&](int i) { return __builtin_amdgcn_readfirstlane(next_lds[i]); };
+          next_unit = word(0);
+          next_it.entry = word(4);
+          next_it.row0 = word(5);
+          next_it.nrows = word(6);
+          next_it.kv_lo = word(7);
+          next_it.kv_hi = word(8);
+          next_it.part_row0 = word(9);
+          next_e.seg_begin = word(12);
+          next_e.seg_end = word(13);
+          next_e.n = word(14);
+          next_e.delta = word(15);
+          next_e.tok0 = word(16);
+        }
+        next_g = next_unit % c.n_kv_heads;
+        // every wavefront is past its key loop: its first stage may take the next unit's first tile, and no
+        // wavefront reads the current unit's Q any more
+        if (next_unit >= 0) {
+          open_keys(next_it, next_e, next_g);  // (have0, t0, cur now belong to the next unit)
+          open_q(next_it, next_e, next_g);
+        }
       }
       const int row = mb * 32 + (lane & 31);
       float mw[4], lw[4];
@@ -410,10 +484,11 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
 }  // namespace mfma
 
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
-                                int32_t max_rows, hipStream_t stream) {
+                                int32_t max_rows, int32_t* queue, int32_t n_units, hipStream_t stream) {
   using namespace mfma;
   if (n_chains <= 0) return hipSuccess;
   if (a.arena.head_dim != D || a.arena.dtype != 1 || max_rows > 64) return hipErrorInvalidValue;
+  if (queue && a.inline_blob) return hipErrorInvalidValue;  // the queue's counter needs device memory
   // once per process, whatever thread or pool gets here first
   static std::once_flag attr_once;
   static hipError_t attr_status = hipSuccess;
@@ -429,12 +504,12 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const 
   const dim3 grid((unsigned)n_chains);
   if (a.inline_blob) {
     BlobArg<true> blob{*a.inline_blob};
-    if (max_rows <= 32) attend_stream_kernel<1, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains);
-    else attend_stream_kernel<2, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains);
+    if (max_rows <= 32) attend_stream_kernel<1, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
+    else attend_stream_kernel<2, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
   } else {
     const BlobArg<false> none{0};
-    if (max_rows <= 32) attend_stream_kernel<1, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains);
-    else attend_stream_kernel<2, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains);
+    if (max_rows <= 32) attend_stream_kernel<1, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
+    else attend_stream_kernel<2, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
   }
   return hipGetLastError();
 }

@@ -66,11 +66,14 @@ hipError_t launch_attend_ref(const AttendArgs& a, hipStream_t stream);
 // is negative; every chain holds at least one item.
 hipError_t launch_attend_tile(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
                               hipStream_t stream);
-// Unit u = item u / n_kv_heads for KV head u % n_kv_heads.  Workgroup w walks the chain links[w],
-// links[n_chains + that unit], ... until a link is negative.
+// Unit u = item u / n_kv_heads for KV head u % n_kv_heads; n_chains workgroups.
+// queue == nullptr: workgroup w walks the chain links[w], links[n_chains + that unit], ... until a link is negative.
+// queue != nullptr (DEVICE int32, holding n_chains when the kernel starts; not with an inline blob): workgroup w
+// starts with unit w and draws every further unit from the counter (atomic add) until it reaches n_units; the
+// units are expected longest first.  `links` is not read then.
 // max_rows: the largest DkItem::nrows among the items (at most 64).
 hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const int32_t* links, int32_t n_chains,
-                                int32_t max_rows, hipStream_t stream);
+                                int32_t max_rows, int32_t* queue, int32_t n_units, hipStream_t stream);
 // max_rows: the largest DkMerge::nrows among them (sizes the grid).
 hipError_t launch_attend_merge(const AttendArgs& a, const DkMerge* merges, int32_t n_merges, int32_t max_rows,
                                hipStream_t stream);

@@ -25,6 +25,8 @@ struct PlanConfig {
   int32_t stream_chains;     // workgroups of the streaming kernel: one per compute unit
   int32_t stream_item_cost;  // fixed cost of an item in the chain balance, in keys
   float xcd_speed[8];        // relative K/V streaming rate of the XCD that workgroup w lands on (w % 8)
+  int32_t stream_queue;      // 1: streaming units are drawn from a queue at run time when the blob is uploaded
+  int32_t inline_blob_bytes; // a descriptor blob up to this size travels in the kernel arguments
 };
 
 // One packed row tile of an entry before its key range is cut: rows [row0, row0 + nrows) see keys [0, kv_hi).
@@ -60,6 +62,11 @@ struct AttendPlan {
   // chain stream_links[w], stream_links[n_chains + that unit], ... until a link is negative.
   std::vector<int32_t> stream_links;
   int32_t stream_chains = 0;
+  // ... or, when stream_queued, starts with unit w and draws every further unit from a counter (off_queue, one
+  // int32 that is uploaded holding stream_chains): the units are in longest-first order, no links are built.
+  bool stream_queued = false;
+  int64_t stream_units = 0;
+  size_t off_queue = 0;
   // Tile kernel: tile_wave_slots workgroups per KV head, workgroup c of a head walks the items
   // tile_links[c], tile_links[tile_chains + that item], ...; the chains are the same for every KV head.
   std::vector<int32_t> tile_links;

@@ -71,10 +71,32 @@ static void run_case(const Case& cs, int hq, int hkv, const float* speeds, doubl
   if (speeds)
     for (int x = 0; x < 8; ++x) cfg.xcd_speed[x] = speeds[x];
   dk::AttendPlan p;
+  {  // the same batch with the streaming units drawn from a queue at run time: no links, units longest first, and
+     // only for launches whose descriptors cannot travel in the kernel arguments
+    dk::PlanConfig qcfg = cfg;
+    qcfg.stream_queue = 1;
+    qcfg.inline_blob_bytes = 3072;
+    std::lock_guard<std::mutex> g(pool.mutex());
+    CHECK(dk::build_plan(pool, qcfg, nseq, slots.data(), cu.data(), /*staged=*/true, &p) == dk::OK);
+    const int64_t units = (int64_t)p.stream_items.size() * hkv;
+    CHECK(p.stream_units == units);
+    if (p.stream_queued) {
+      CHECK(units >= 4 * (int64_t)qcfg.stream_chains && p.blob_bytes > 3072);
+      CHECK(p.stream_links.empty() && p.stream_chains == qcfg.stream_chains);
+      CHECK(p.off_queue % 16 == 0 && p.off_queue + 16 <= p.blob_bytes);
+      for (size_t i = 1; i < p.stream_items.size(); ++i) {
+        const DkItem &a = p.stream_items[i - 1], &b = p.stream_items[i];
+        CHECK((int64_t)(a.kv_hi - a.kv_lo) * a.nrows >= (int64_t)(b.kv_hi - b.kv_lo) * b.nrows);
+      }
+    } else {
+      CHECK(units < 4 * (int64_t)qcfg.stream_chains || p.entries.size() * sizeof(DkEntry) <= 3072);
+    }
+  }
   {
     std::lock_guard<std::mutex> g(pool.mutex());
     CHECK(dk::build_plan(pool, cfg, nseq, slots.data(), cu.data(), /*staged=*/true, &p) == dk::OK);
   }
+  CHECK(!p.stream_queued);
   CHECK((int)p.entries.size() == nseq);
   std::map<std::pair<int, int>, std::vector<std::pair<int, int>>> cover;
   check_cover(p, cfg, p.tile_items, cfg.tile_rows, &cover);
