@@ -455,6 +455,30 @@ def test_append_attend_that_does_not_fit_changes_nothing():
     m.pool.close()
 
 
+def test_queued_and_planned_units_give_identical_bits():
+    """Which workgroup computes a streaming unit -- drawn from the run-time queue, or walked in a chain planned on the
+    host -- has no influence on the unit's result: the same batch under both settings, bit for bit."""
+    sh = wl.PRODUCTION
+    rng = np.random.default_rng(31)
+    n_slots = 200  # 1600 units: queued by default
+    m = Mirror(sh, n_slots, n_slots * 700 + 4096, granule=64, seed=3)
+    slots = [m.acquire() for _ in range(n_slots)]
+    hist = rng.integers(1, 600, size=n_slots).tolist()
+    m.append(slots, hist)
+    deltas = rng.integers(1, 10, size=n_slots).tolist()
+    q = m.draw(sum(deltas), sh.n_q_heads)
+    m.append(slots, deltas)
+    out_q, _, _ = m.attend_appended(slots, deltas, q)
+    dk.set_tuning(m.pool.handle, "stream_queue", 0)
+    out_c, _, _ = m.attend_appended(slots, deltas, q)
+    dk.set_tuning(m.pool.handle, "stream_queue", 1)
+    out_q2, _, _ = m.attend_appended(slots, deltas, q)
+    assert torch.equal(out_q, out_c) and torch.equal(out_q, out_q2)
+    ref, _ = m.oracle_appended(slots, deltas, q)
+    check_close(out_q, ref, sh.dtype, "queued units", row_scaled=True)
+    m.pool.close()
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_chains_of_streaming_units_with_one_and_two_row_blocks(seed):
     """Hundreds of slots with Delta from 0 up to the streaming kernel's limit (64 packed rows: both its one-block
