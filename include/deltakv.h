@@ -344,8 +344,9 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
  *   stream_min_chunk  smallest key range worth its own streaming item               [64, 2^24]     default 512
  *   stream_chains     workgroups of the streaming kernel (one per compute unit)     [1, 65536]     default 256
  *   stream_item_cost  fixed cost of a streaming unit in the chain balance, in keys  [0, 2^20]      default 512
- *   stream_queue      1: with four or more units per streaming workgroup the units   {0, 1}         default 1
+ *   stream_queue      1: with four or more units per streaming workgroup the units   {0, 1, 2}      default 1
  *                     are drawn from a queue at run time (longest first);
+ *                     2: already with more units than workgroups;
  *                     0: the workgroups always walk chains balanced on the host
  *   tile_wave_slots   tile-kernel workgroups of one KV head that run at a time      [1, 65536]     default 256 / Hkv
  *   tile_min_chunk    smallest key range worth its own tile item                    [64, 2^24]     default 128

@@ -246,7 +246,7 @@ int32_t dk_set_tuning(dk_pool* pool, const char* name, double value) {
   if (key == "stream_min_chunk") return whole(64, 1 << 24, &c.stream_min_chunk);
   if (key == "stream_chains") return whole(1, 1 << 16, &c.stream_chains);
   if (key == "stream_item_cost") return whole(0, 1 << 20, &c.stream_item_cost);
-  if (key == "stream_queue") return whole(0, 1, &c.stream_queue);
+  if (key == "stream_queue") return whole(0, 2, &c.stream_queue);
   if (key == "tile_wave_slots") return whole(1, 1 << 16, &c.tile_wave_slots);
   if (key == "tile_min_chunk") return whole(64, 1 << 24, &c.tile_min_chunk);
   if (key == "tile_item_cost") return whole(0, 1 << 16, &c.tile_item_cost);

@@ -301,8 +301,9 @@ int32_t build_plan(Pool& pool, const PlanConfig& cfg, int32_t n_seqs, const int3
   p->stream_units = (int64_t)p->stream_items.size() * cfg.n_kv_heads;
   const size_t floor_bytes = p->entries.size() * sizeof(DkEntry) + p->segs.size() * sizeof(DkSeg) +
                              (p->tile_items.size() + p->stream_items.size()) * sizeof(DkItem);
-  p->stream_queued = cfg.stream_queue != 0 && p->stream_units >= 4 * (int64_t)std::max(cfg.stream_chains, 1) &&
-                     floor_bytes > (size_t)cfg.inline_blob_bytes;
+  const int64_t per_wg = cfg.stream_queue == 2 ? 1 : 4;  // (2: queue whenever some workgroup gets a second unit)
+  p->stream_queued = cfg.stream_queue != 0 && p->stream_units >= per_wg * (int64_t)std::max(cfg.stream_chains, 1) &&
+                     p->stream_units > std::max(cfg.stream_chains, 1) && floor_bytes > (size_t)cfg.inline_blob_bytes;
   if (p->stream_queued) {
     p->stream_links.clear();
     p->stream_chains = (int32_t)std::min<int64_t>(p->stream_units, std::max(cfg.stream_chains, 1));
