@@ -351,7 +351,8 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
  *   tile_wave_slots   tile-kernel workgroups of one KV head that run at a time      [1, 65536]     default 256 / Hkv
  *   tile_min_chunk    smallest key range worth its own tile item                    [64, 2^24]     default 128
  *   tile_item_cost    fixed cost of a tile item inside a chain, in 64-key tiles     [0, 65536]     default 5
- *   xcd_speed0 .. xcd_speed7  relative K/V streaming rate of each XCD               (0, 100]       default 1
+ *   xcd_speed0 .. xcd_speed7  relative K/V streaming rate of each XCD, used when    (0, 100]       default 1 (even),
+ *                     streaming chains are balanced on the host                                      0.95 (odd)
  * Affects only how later calls cut and order their work, never their results' meaning.
  */
 int32_t dk_set_tuning(dk_pool* pool, const char* name, double value);
