@@ -15,7 +15,8 @@
  *     NULL = the default stream).  They never wait for the device and never allocate
  *     device or pinned memory: descriptors travel through the caller's staging memory
  *     (dk_pool_desc::host_staging), and a call that finds every staging buffer still
- *     in flight returns DK_ERR_BUSY instead of waiting.  They read the slot metadata
+ *     in flight returns DK_ERR_BUSY instead of waiting (dk_staging_wait is the matching wait).
+ *     They read the slot metadata
  *     at call time, so later host-side calls (trim, release, alias) do not affect
  *     work already enqueued.  All GPU-launching calls on one pool must be issued on
  *     one stream, or be ordered by the caller;
@@ -333,6 +334,14 @@ int32_t dk_seq_cells(dk_pool* pool, int32_t slot, int64_t* cells_out, int64_t ca
 int32_t dk_seq_gather(dk_pool* pool, int32_t slot, void* k_out, void* v_out, void* stream);
 int32_t dk_pool_stats(dk_pool* pool, int64_t* cells_held_out, int64_t* cells_free_out);
 int32_t dk_seq_stats(dk_pool* pool, int32_t slot, int64_t* segments_out, int64_t* chain_nodes_out);
+
+/*
+ * Back-pressure for a caller that got DK_ERR_BUSY: blocks the calling HOST thread until the staging buffer that the
+ * next launching call would take is free again (the upload that last used it has run), and no longer -- work queued
+ * behind that upload keeps the device busy meanwhile, unlike after a stream synchronisation.  The only call besides
+ * dk_pool_destroy and dk_attend_times that waits.  DK_ERR_WORKSPACE for a pool without staging memory.
+ */
+int32_t dk_staging_wait(dk_pool* pool);
 
 /* Kernel selection for dk_delta_attend: 0 automatic (default), 1 force the scalar reference kernel. */
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);

@@ -63,6 +63,7 @@ SIGNATURES = {
                                      C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "dk_delta_attend_noalloc": (C.c_int32, [C.c_void_p, C.c_int32, _I32P, _I32P, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dk_staging_wait": (C.c_int32, [C.c_void_p]),
     "dk_seq_cells": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, C.c_int64]),
     "dk_seq_gather": (C.c_int32, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dk_seq_stats": (C.c_int32, [C.c_void_p, C.c_int32, _I64P, _I64P]),
@@ -155,14 +156,18 @@ def set_tuning(pool, name: str, value: float) -> None:
 
 
 def _launch(call, where: str, pool, stream):
-    """Runs a launching call; when every staging buffer is still in flight (BUSY) waits for the stream and repeats.
+    """Runs a launching call; when every staging buffer is still in flight (BUSY) waits for one to come free and repeats.
     The C ABI itself never waits: back-pressure is the caller's policy, and this is the binding's."""
     rc = call()
     while rc == BUSY:
-        import torch
-        (torch.cuda.current_stream() if stream is None else stream).synchronize()
+        # wait for the oldest upload only: the work queued behind it keeps the device busy meanwhile
+        _check(lib().dk_staging_wait(pool), "staging_wait", pool)
         rc = call()
     _check(rc, where, pool)
+
+
+def staging_wait(pool) -> None:
+    _check(lib().dk_staging_wait(pool), "staging_wait", pool)
 
 
 def pool_create(desc: PoolDesc) -> C.c_void_p:

@@ -750,6 +750,21 @@ int32_t dk_verify_greedy(int32_t n_seqs, int32_t total_rows, const int32_t* cu_d
   return e == hipSuccess ? DK_OK : DK_ERR_HIP;
 }
 
+int32_t dk_staging_wait(dk_pool* pool) {
+  if (!pool) return DK_ERR_INVALID;
+  // (The event is read under the lock and waited for outside it: other threads may go on launching.)
+  hipEvent_t ev = nullptr;
+  {
+    std::lock_guard<std::mutex> launch(pool->launch_mu);
+    if (pool->ring_size == 0) return DK_ERR_WORKSPACE;
+    Staging& s = pool->ring[pool->ring_next];
+    if (!s.in_flight) return DK_OK;
+    ev = s.done;
+  }
+  const hipError_t e = hipEventSynchronize(ev);
+  return e == hipSuccess ? DK_OK : pool->hip_fail(e);
+}
+
 int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant) {
   if (!pool || variant < 0 || variant > 1) return DK_ERR_INVALID;
   pool->variant = variant;

@@ -16,7 +16,8 @@ class DevicePool:
     """Owns the device buffers of one pool and forwards to the C ABI."""
 
     def __init__(self, n_slots: int, arena_cells: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
-                 dtype: str = "bf16", n_session_slots: int = 0, granule_cells: int = 0, device: str = "cuda:0"):
+                 dtype: str = "bf16", n_session_slots: int = 0, granule_cells: int = 0, device: str = "cuda:0",
+                 staging_depth: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("deltakv needs a GPU: no CPU fallback exists")
         self.device = torch.device(device)
@@ -29,7 +30,7 @@ class DevicePool:
         self.v_arena = torch.empty_like(self.k_arena)
         desc = dk.PoolDesc(n_slots, n_session_slots, arena_cells, granule_cells, n_q_heads, n_kv_heads, head_dim,
                            dk.BF16 if dtype == "bf16" else dk.F32, self.k_arena.data_ptr(), self.v_arena.data_ptr(),
-                           None, 0, None, 0, 0)
+                           None, 0, None, 0, staging_depth)
         nbytes = dk.meta_bytes(desc)
         self.dev_meta = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         desc.dev_meta = self.dev_meta.data_ptr()

@@ -455,6 +455,46 @@ def test_append_attend_that_does_not_fit_changes_nothing():
     m.pool.close()
 
 
+def test_busy_staging_ring_and_the_matching_wait():
+    """Two staging buffers and calls whose descriptors need an upload: a launching call that finds both buffers in
+    flight reports BUSY and enqueues nothing; after dk_staging_wait the same call goes through, and the results of
+    all calls are right.  (Whether BUSY shows up depends on how far the host gets ahead of the device, so it is
+    provoked with a long queue, but only its consequences are asserted.)"""
+    from paper_2605_26289_amd import DevicePool
+    sh = wl.PRODUCTION
+    n_slots, n = 96, 3000
+    pool = DevicePool(n_slots, n_slots * (n + 512), sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, staging_depth=2)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    slots = [pool.acquire() for _ in range(n_slots)]
+    kv = torch.randn((n, sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    for s_ in slots:
+        pool.append([s_], [0, n], kv, kv)
+    cu = np.arange(n_slots + 1, dtype=np.int32) * 3
+    q = torch.randn((int(cu[-1]), sh.n_q_heads, sh.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    kn = torch.randn((int(cu[-1]), sh.n_kv_heads, sh.head_dim), generator=gen, device="cuda").to(torch.bfloat16)
+    ws = pool.ensure_workspace(slots, cu, True)
+    outs = [torch.empty_like(q) for _ in range(24)]
+    s_arr, s_p = dk._i32(slots)
+    c_arr, c_p = dk._i32(cu)
+    busy = 0
+    torch.cuda.synchronize()
+    for out in outs:
+        call = lambda: dk.lib().dk_delta_attend(pool.handle, n_slots, s_p, c_p, q.data_ptr(), kn.data_ptr(), kn.data_ptr(),  # noqa: E731
+                                                float(sh.scale), out.data_ptr(), None, ws.data_ptr(), ws.numel(), None)
+        rc = call()
+        if rc == dk.BUSY:
+            busy += 1
+            dk.staging_wait(pool.handle)
+            rc = call()  # the buffer this call takes is free now, whatever else is still queued
+        assert rc == 0, rc
+    torch.cuda.synchronize()
+    for out in outs[1:]:
+        assert torch.equal(out, outs[0])
+    print(f"[busy] {busy} of {len(outs)} calls found the ring full")
+    pool.close()
+
+
 def test_queued_and_planned_units_give_identical_bits():
     """Which workgroup computes a streaming unit -- drawn from the run-time queue, or walked in a chain planned on the
     host -- has no influence on the unit's result: the same batch under both settings, bit for bit."""
