@@ -94,6 +94,9 @@ def test_launching_calls_without_staging_memory_report_workspace():
                   "kv_append")
     assert e.value.name == "WORKSPACE"
     assert dk.seq_len(p, s) == 0 and dk.pool_stats(p)[0] == 0
+    with pytest.raises(dk.DeltaKVError, match="WORKSPACE"):  # nothing to wait for either
+        dk.staging_wait(p)
+    assert dk.lib().dk_staging_wait(None) == -1
     dk.pool_destroy(p)
 
 
