@@ -69,6 +69,26 @@ def test_no_alloc_entry_point_equals_delta_attend_on_two_calls_in_a_row():
     m.pool.close()
 
 
+def test_no_alloc_entry_point_with_units_drawn_from_the_queue():
+    """A decode batch with enough streaming units for the run-time queue: its counter lives in the built-in array
+    too, is set by every call's descriptor upload, and two calls in a row give dk_delta_attend's bits."""
+    sh = wl.PRODUCTION
+    n_slots = 160  # 1280 units
+    rng = np.random.default_rng(7)
+    m = Mirror(sh, n_slots, n_slots * 600 + 4096, granule=64, seed=105)
+    slots = [m.acquire() for _ in range(n_slots)]
+    m.append(slots, rng.integers(1, 400, size=n_slots).tolist())
+    for turn in range(2):
+        deltas = rng.integers(1, 5, size=n_slots).tolist()
+        m.append(slots, deltas)
+        q = m.draw(sum(deltas), sh.n_q_heads)
+        out_a, out_b, lse_a, lse_b, _ = _both_ways(m, slots, deltas, q)
+        assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b)
+        ref, _ = m.oracle_appended(slots, deltas, q)
+        check_close(out_a, ref, sh.dtype, f"no-alloc queued call {turn}", row_scaled=True)
+    m.pool.close()
+
+
 def test_no_alloc_entry_point_turns_down_what_its_scratch_cannot_hold():
     """A single long session whose key range is split many ways needs more partial rows than the built-in array
     holds: the call reports WORKSPACE, launches nothing and leaves the output untouched."""
