@@ -349,6 +349,8 @@ int32_t dk_set_attend_variant(dk_pool* pool, int32_t variant);
  * Planner tuning, per pool; the defaults suit an MI355X (256 compute units in 8 XCDs) and the library
  * reads no environment variable.  Names and ranges (DK_ERR_UNSUPPORTED for an unknown name,
  * DK_ERR_INVALID for a value out of range or not whole where a count is meant):
+ *   stream_rows       most packed query rows (G * Delta) of a sequence that still    [32, 96]       default 96
+ *                     goes to the streaming kernel (more: the tile kernel)
  *   stream_target     aimed number of streaming work items per KV head             [1, 2^20]      default 256 / Hkv
  *   stream_min_chunk  smallest key range worth its own streaming item               [64, 2^24]     default 512
  *   stream_chains     workgroups of the streaming kernel (one per compute unit)     [1, 65536]     default 256

@@ -204,7 +204,7 @@ int32_t dk_pool_create(const dk_pool_desc* desc, dk_pool** pool_out) {
     c.head_dim = desc->head_dim;
     c.use_mfma = desc->dtype == DK_BF16 && desc->head_dim == 128 && is_pow2(group) && group <= 16;
     c.tile_rows = 256;
-    c.stream_rows = 64;
+    c.stream_rows = 96;
     c.kv_tile = 64;
     // stream items: never cut a slot's keys finer than one CU's fair share of the batch (256 CUs); every extra
     // item costs a ramp-up, a partial write and merge work, and the planner's chains balance the rest
@@ -244,6 +244,7 @@ int32_t dk_set_tuning(dk_pool* pool, const char* name, double value) {
     *dst = (int32_t)value;
     return DK_OK;
   };
+  if (key == "stream_rows") return whole(32, 96, &c.stream_rows);
   if (key == "stream_target") return whole(1, 1 << 20, &c.stream_target);
   if (key == "stream_min_chunk") return whole(64, 1 << 24, &c.stream_min_chunk);
   if (key == "stream_chains") return whole(1, 1 << 16, &c.stream_chains);

@@ -8,7 +8,7 @@
 //
 //   tile kernel    large Delta: a workgroup owns 256 packed rows (4 wavefronts x 64 rows) and all
 //                  wavefronts share each 64-key K/V tile through LDS (compute bound, MFMA roofline)
-//   stream kernel  small Delta (G*Delta <= 64): every wavefront streams its own slice of the keys
+//   stream kernel  small Delta (G*Delta <= 96): every wavefront streams its own slice of the keys
 //                  through private LDS stages with no barriers, the four states are merged at the
 //                  end (HBM bound)
 //
@@ -66,12 +66,54 @@ __device__ __forceinline__ float stream_max3(float a, float b, float c) {
   return d;
 }
 
-// One 32-key tile against MB*32 query rows, operands in registers: S^T, online softmax, O^T update.
-// Q as B operand: lane (row l%32 of block mb, half l/32) holds Q[row][ks*16 + 8*(l/32) .. +7].
+// O *= alpha for one accumulator, written so that the accumulators stay in the accumulation registers: with plain
+// C++ here the compiler keeps a second copy of all of O in ordinary registers, refreshed for every tile (one
+// v_accvgpr_read per element and tile) only to serve this rarely taken path.  Every MFMA that wrote O has retired
+// by the time this runs: the scores of the current tile, produced by later MFMAs, have already been read.
+__device__ __forceinline__ float scale_acc(float o, float alpha) {
+  float t;
+  asm volatile(
+      "v_accvgpr_read_b32 %1, %0\n\t"
+      "s_nop 0\n\t"
+      "v_mul_f32 %1, %1, %2\n\t"
+      "s_nop 0\n\t"
+      "v_accvgpr_write_b32 %0, %1"
+      : "+a"(o), "=&v"(t)
+      : "v"(alpha));
+  return o;
+}
+
+// Q as B operand: lane (row l%32 of block mb, half l/32) holds Q[row][ks*16 + 8*(l/32) .. +7].  With one or two
+// row blocks the unit's Q fragments stay in registers for the whole unit; with three (96 registers next to 192
+// of accumulators) they would not fit, so each tile reads them from the Q area in LDS again (24 ds_read_b128 per
+// tile next to the tile's own 16: LDS bandwidth is idle here).
 template <int MB>
-__device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&qf)[MB][8], RowState<MB>& st,
+struct QFrags {
+  static constexpr bool IN_LDS = MB > 2;
+  bf16x8 r[IN_LDS ? 1 : MB][8];
+  const char* q_lds;
+  uint32_t koff;
+  __device__ __forceinline__ void load() {
+    if constexpr (!IN_LDS) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) r[mb][ks] = read_k_frag(q_lds, koff, mb, ks);
+    }
+  }
+  __device__ __forceinline__ bf16x8 get(int mb, int ks) const {
+    if constexpr (IN_LDS) return read_k_frag(q_lds, koff, mb, ks);
+    else return r[mb][ks];
+  }
+};
+
+// One 32-key tile against MB*32 query rows, operands in registers: S^T, online softmax, O^T update.
+template <int MB>
+__device__ __forceinline__ void compute_tile(const TileFrags& f, const QFrags<MB>& qf, RowState<MB>& st,
                                              const int (&limit)[MB], float c, int lane, int cnt, int pos,
                                              bool need_mask) {
+  const int h = lane >> 5;
+  bf16x8 pf[MB][2];
   f32x16 s[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -80,9 +122,8 @@ __device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.k[ks], qf[mb][ks], s[mb], 0, 0, 0);
+    for (int mb = 0; mb < MB; ++mb) s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.k[ks], qf.get(mb, ks), s[mb], 0, 0, 0);
 
-  const int h = lane >> 5;
   if (need_mask) {
     // accumulator r is key 8*(r/4) + 4h + r%4 of the tile
 #pragma unroll
@@ -121,11 +162,10 @@ __device__ __forceinline__ void compute_tile(const TileFrags& f, const bf16x8 (&
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[db][mb][r] *= alpha;
+        for (int r = 0; r < 16; ++r) st.o[db][mb][r] = scale_acc(st.o[db][mb][r], alpha);
     }
   }
 
-  bf16x8 pf[MB][2];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     const float ms = (st.m[mb] == -INFINITY) ? 0.f : st.m[mb];
@@ -183,8 +223,10 @@ constexpr int STREAM_KT = 32;
 constexpr int STREAM_STAGE_BYTES = 2 * STREAM_KT * ROW_BYTES;  // 16 KiB
 constexpr int STREAM_WAVE_BYTES = 2 * STREAM_STAGE_BYTES;      // 32 KiB
 constexpr int STREAM_ML_OFFSET = 4 * STREAM_WAVE_BYTES;        // after the stages
-constexpr int STREAM_Q_OFFSET = STREAM_ML_OFFSET + 4 * 64 * 2 * 4;
-constexpr int STREAM_NEXT_OFFSET = STREAM_Q_OFFSET + 2 * 32 * ROW_BYTES;
+constexpr int STREAM_MAX_MB = 3;                               // row blocks of the widest instantiation
+constexpr int STREAM_ML_ROWS = STREAM_MAX_MB * 32;             // rows per wavefront in the (m, l) exchange
+constexpr int STREAM_Q_OFFSET = STREAM_ML_OFFSET + 4 * STREAM_ML_ROWS * 2 * 4;
+constexpr int STREAM_NEXT_OFFSET = STREAM_Q_OFFSET + STREAM_MAX_MB * 32 * ROW_BYTES;
 constexpr int STREAM_LDS_BYTES = STREAM_NEXT_OFFSET + 128;
 
 // One wavefront moves 4 query rows (1 KiB) HBM -> LDS into the Q area: packed row `blk * 4 + l / 16` of the
@@ -218,7 +260,9 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // MB = 32-row blocks per unit: 1 when no unit of the launch has more than 32 packed rows (Delta <= 32 / G:
-// decode and short verify steps then skip the second, all-padding block), else 2.
+// decode and short verify steps then skip the all-padding blocks), 2 up to 64 rows, else 3 (up to 96 rows: between
+// 64 and 96 rows a unit is still far below the MFMA/HBM ridge, and the tile kernel, built for 256-row tiles, keeps
+// too little in flight to stream it well).
 // INLINE: the descriptors arrive inside the kernel arguments (first argument) and the descriptor pointers are byte
 // offsets into them; otherwise they point into the uploaded workspace.
 template <int MB, bool INLINE>
@@ -233,7 +277,7 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   char* my = smem + wave * STREAM_WAVE_BYTES;
-  float* ml = (float*)(smem + STREAM_ML_OFFSET);  // [wave][row 0..63][m, l]
+  float* ml = (float*)(smem + STREAM_ML_OFFSET);  // [wave][row 0..95][m, l]
   char* q_lds = smem + STREAM_Q_OFFSET;
   int32_t* next_lds = (int32_t*)(smem + STREAM_NEXT_OFFSET);  // [0] unit, [4..11] its DkItem, [12..19] its DkEntry
   const uint32_t koff = k_lane_off(lane);
@@ -327,11 +371,10 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
     // Everything requested before the second tile has arrived: the unit's Q rows and its first tile.
     if (wave == 0) DK_STR(trace_seq, 0);
     if (have1) wait_vmcnt<16>(); else wait_vmcnt<0>();
-    bf16x8 qf[MB][8];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) qf[mb][ks] = read_k_frag(q_lds, koff, mb, ks);
+    QFrags<MB> qf;
+    qf.q_lds = q_lds;
+    qf.koff = koff;
+    qf.load();
     if (wave == 0) DK_STR(trace_seq, 1);
 
     // Two private stages per wavefront.  A tile's fragments are read into registers as soon as it has
@@ -396,14 +439,12 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
     for (int mb = 0; mb < MB; ++mb) {
       const float lt = st.l[mb] + __shfl_xor(st.l[mb], 32);
       if (lane < 32) {
-        ml[(wave * 64 + mb * 32 + lane) * 2] = st.m[mb];
-        ml[(wave * 64 + mb * 32 + lane) * 2 + 1] = lt;
+        ml[(wave * STREAM_ML_ROWS + mb * 32 + lane) * 2] = st.m[mb];
+        ml[(wave * STREAM_ML_ROWS + mb * 32 + lane) * 2 + 1] = lt;
       }
     }
     int next_g = 0;
     const int db = wave;
-    f32x16 acc[MB];
-    float mm[MB], ll[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       // row block mb of every wavefront's O goes through the wavefronts' second stages: [db][r][lane]
@@ -443,29 +484,30 @@ __global__ __launch_bounds__(256, 1) void attend_stream_kernel(BlobArg<INLINE> b
       float mx = -INFINITY;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        mw[w] = ml[(w * 64 + row) * 2];
-        lw[w] = ml[(w * 64 + row) * 2 + 1];
+        mw[w] = ml[(w * STREAM_ML_ROWS + row) * 2];
+        lw[w] = ml[(w * STREAM_ML_ROWS + row) * 2 + 1];
         mx = fmaxf(mx, mw[w]);
       }
       const float ms = (mx == -INFINITY) ? 0.f : mx;
       float lsum = 0.f;
+      f32x16 acc[1];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[0][r] = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const float f = __builtin_amdgcn_exp2f(mw[w] - ms);
         lsum += f * lw[w];
         const float* theirs = (const float*)(smem + w * STREAM_WAVE_BYTES + STREAM_STAGE_BYTES);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][r] += f * theirs[(db * 16 + r) * 64 + lane];
+        for (int r = 0; r < 16; ++r) acc[0][r] += f * theirs[(db * 16 + r) * 64 + lane];
       }
-      mm[mb] = mx;
-      ll[mb] = lsum;
       // the buffer has been read everywhere: the next row block, or the next unit's second tile, may overwrite it
       if (mb + 1 < MB || next_unit >= 0) lds_barrier();
+      // (one row block's result at a time: the merged rows of all blocks together would not fit the registers)
+      const float mm[1] = {mx}, ll[1] = {lsum};
+      store_block<1>(c, e, it, g, mb * 32, lane, db, acc, ll);
+      if (wave == 0) store_ml<1>(c, e, it, g, mb * 32, lane, mm, ll);
     }
-    store_block<MB>(c, e, it, g, 0, lane, db, acc, ll);
-    if (wave == 0) store_ml<MB>(c, e, it, g, 0, lane, mm, ll);
     // (after the stores: the wait that opens the next unit lets exactly this request stay in flight)
     if (next_unit >= 0) open_second(next_g);
     if (wave == 0) DK_STR(trace_seq, 7);
@@ -487,14 +529,15 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const 
                                 int32_t max_rows, int32_t* queue, int32_t n_units, hipStream_t stream) {
   using namespace mfma;
   if (n_chains <= 0) return hipSuccess;
-  if (a.arena.head_dim != D || a.arena.dtype != 1 || max_rows > 64) return hipErrorInvalidValue;
+  if (a.arena.head_dim != D || a.arena.dtype != 1 || max_rows > STREAM_MAX_MB * 32) return hipErrorInvalidValue;
   if (queue && a.inline_blob) return hipErrorInvalidValue;  // the queue's counter needs device memory
   // once per process, whatever thread or pool gets here first
   static std::once_flag attr_once;
   static hipError_t attr_status = hipSuccess;
   std::call_once(attr_once, [] {
-    const void* kernels[4] = {(const void*)attend_stream_kernel<1, false>, (const void*)attend_stream_kernel<1, true>,
-                              (const void*)attend_stream_kernel<2, false>, (const void*)attend_stream_kernel<2, true>};
+    const void* kernels[6] = {(const void*)attend_stream_kernel<1, false>, (const void*)attend_stream_kernel<1, true>,
+                              (const void*)attend_stream_kernel<2, false>, (const void*)attend_stream_kernel<2, true>,
+                              (const void*)attend_stream_kernel<3, false>, (const void*)attend_stream_kernel<3, true>};
     for (const void* k : kernels)
       if (attr_status == hipSuccess)
         attr_status = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, STREAM_LDS_BYTES);
@@ -505,11 +548,13 @@ hipError_t launch_attend_stream(const AttendArgs& a, const DkItem* items, const 
   if (a.inline_blob) {
     BlobArg<true> blob{*a.inline_blob};
     if (max_rows <= 32) attend_stream_kernel<1, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
-    else attend_stream_kernel<2, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
+    else if (max_rows <= 64) attend_stream_kernel<2, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
+    else attend_stream_kernel<3, true><<<grid, 256, STREAM_LDS_BYTES, stream>>>(blob, c, links, n_chains, queue, n_units);
   } else {
     const BlobArg<false> none{0};
     if (max_rows <= 32) attend_stream_kernel<1, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
-    else attend_stream_kernel<2, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
+    else if (max_rows <= 64) attend_stream_kernel<2, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
+    else attend_stream_kernel<3, false><<<grid, 256, STREAM_LDS_BYTES, stream>>>(none, c, links, n_chains, queue, n_units);
   }
   return hipGetLastError();
 }

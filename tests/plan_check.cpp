@@ -27,7 +27,7 @@ static dk::PlanConfig config(int hq, int hkv) {
   c.head_dim = 128;
   c.use_mfma = true;
   c.tile_rows = 256;
-  c.stream_rows = 64;
+  c.stream_rows = 96;
   c.kv_tile = 64;
   c.tile_wave_slots = 256 / hkv;
   c.stream_target = 256 / hkv;

@@ -114,7 +114,7 @@ def test_config5_scaled_spec_verify(variant):
 
 @pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("n,delta", [(0, 1), (0, 5), (1, 1), (63, 1), (64, 2), (65, 16), (200, 17), (3, 70), (0, 300),
-                                     (129, 64), (1000, 9), (257, 130)])
+                                     (129, 64), (1000, 9), (257, 130), (0, 20), (31, 21), (200, 24), (1000, 22)])
 def test_edge_shapes_appended_and_staged_agree_with_oracle(n, delta, variant):
     sh = SMALL
     m = Mirror(sh, 2, 4096, granule=16, seed=n * 1000 + delta)
@@ -245,11 +245,12 @@ def test_errors_from_gpu_entry_points():
     m.pool.close()
 
 
-@pytest.mark.parametrize("delta", [9, 300])
+@pytest.mark.parametrize("delta", [4, 9, 22, 300])
 def test_growing_scores_exercise_the_lazy_rescale(delta):
     """Keys whose scores keep outgrowing the reference maximum (by far more than the rescale slack, several
     times along the prefix, and again inside the new block): the deferred O rescale of the tile kernel and the
-    conditional rescale of the stream kernel must both land on the oracle's result."""
+    conditional rescale of the stream kernel (one, two and three row blocks) must both land on the oracle's
+    result."""
     sh = SMALL
     m = Mirror(sh, 1, 8192, seed=23)
     s = m.acquire()
@@ -519,24 +520,48 @@ def test_queued_and_planned_units_give_identical_bits():
     m.pool.close()
 
 
+def test_rows_between_the_kernels_limits_agree_with_the_oracle_in_both_kernels():
+    """Sequences of 65 to 96 packed rows go to the streaming kernel by default and to the tile kernel when the
+    limit is tuned down: both must land on the oracle's result (and within twice the tolerance of each other)."""
+    sh = wl.PRODUCTION
+    group = sh.n_q_heads // sh.n_kv_heads
+    rng = np.random.default_rng(47)
+    n_slots = 24
+    m = Mirror(sh, n_slots, n_slots * 2300 + 4096, granule=64, seed=47)
+    slots = [m.acquire() for _ in range(n_slots)]
+    hist = rng.integers(1, 2200, size=n_slots).tolist()
+    m.append(slots, hist)
+    deltas = rng.integers(64 // group + 1, 96 // group + 1, size=n_slots).tolist()
+    q = m.draw(sum(deltas), sh.n_q_heads)
+    m.append(slots, deltas)
+    out_s, lse_s, _ = m.attend_appended(slots, deltas, q, lse=True)
+    dk.set_tuning(m.pool.handle, "stream_rows", 64)
+    out_t, lse_t, _ = m.attend_appended(slots, deltas, q, lse=True)
+    dk.set_tuning(m.pool.handle, "stream_rows", 96)
+    ref, ref_lse = m.oracle_appended(slots, deltas, q)
+    check_close(out_s, ref, sh.dtype, "streaming kernel, three row blocks", row_scaled=True)
+    check_close(out_t, ref, sh.dtype, "tile kernel, fewer than 97 rows", row_scaled=True)
+    assert np.abs(lse_s.cpu().numpy() - ref_lse).max() < 2e-3 and np.abs(lse_t.cpu().numpy() - ref_lse).max() < 2e-3
+    m.pool.close()
+
+
 @pytest.mark.parametrize("seed", range(6))
-def test_chains_of_streaming_units_with_one_and_two_row_blocks(seed):
-    """Hundreds of slots with Delta from 0 up to the streaming kernel's limit (64 packed rows: both its one-block
-    and its two-block form), short and long histories, two turns: every workgroup changes units many times, each
-    change overlapping the next unit's first requests with the merge of the finished one."""
+def test_chains_of_streaming_units_with_one_two_and_three_row_blocks(seed):
+    """Hundreds of slots with Delta from 0 up to the streaming kernel's limit (96 packed rows: its three-block form,
+    with narrower units beside the widest), then up to 64 and up to 32 rows (the two-block and one-block forms),
+    short and long histories: every workgroup changes units many times, each change overlapping the next unit's
+    first requests with the merge of the finished one."""
     rng = np.random.default_rng(77000 + seed)
     sh = (SMALL, wl.PRODUCTION, wl.Shape(16, 4, 128, "bf16"))[seed % 3]
     group = sh.n_q_heads // sh.n_kv_heads
     n_slots = min(int(rng.integers(40, 700)), 250 if sh is wl.PRODUCTION else 700)
     n_hi = int(rng.choice([30, 90, 400, 1500]))
-    m = Mirror(sh, n_slots, n_slots * (n_hi + 40) + 4096, granule=int(rng.choice([16, 64])), seed=seed)
+    m = Mirror(sh, n_slots, n_slots * (n_hi + 60 + 2 * 64) + 4096, granule=int(rng.choice([16, 64])), seed=seed)
     slots = [m.acquire() for _ in range(n_slots)]
     hist = rng.integers(0, n_hi + 1, size=n_slots).tolist()
     m.append([s for s, h in zip(slots, hist) if h], [h for h in hist if h])
-    for turn in range(2):
-        deltas = rng.integers(0, 64 // group + 1, size=n_slots).tolist()
-        if turn == 1:
-            deltas = [min(d, 32 // group) for d in deltas]  # one row block everywhere
+    for turn in range(3):
+        deltas = rng.integers(0, (96, 64, 32)[turn] // group + 1, size=n_slots).tolist()
         q = m.draw(sum(deltas), sh.n_q_heads)
         m.append(slots, deltas)
         out, lse, _ = m.attend_appended(slots, deltas, q, lse=True)
