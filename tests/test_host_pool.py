@@ -75,7 +75,9 @@ def test_tuning_names_and_ranges_and_no_environment_channel(monkeypatch):
     p = _pool()
     dk.set_tuning(p, "stream_chains", 128)
     dk.set_tuning(p, "xcd_speed3", 0.93)
-    for name, value, err in (("stream_chains", 0, "INVALID"), ("stream_chains", 1.5, "INVALID"),
+    dk.set_tuning(p, "stream_rows", 32)
+    dk.set_tuning(p, "stream_rows", 96)
+    for name, value, err in (("stream_chains", 0, "INVALID"), ("stream_rows", 97, "INVALID"), ("stream_rows", 31, "INVALID"), ("stream_chains", 1.5, "INVALID"),
                              ("xcd_speed8", 1.0, "UNSUPPORTED"), ("xcd_speed0", 0.0, "INVALID"),
                              ("no_such_knob", 1, "UNSUPPORTED"), ("tile_min_chunk", 8, "INVALID")):
         with pytest.raises(dk.DeltaKVError) as e:
