@@ -596,7 +596,7 @@ def test_random_batches_match_the_oracle(seed):
                 m.append([s], [int(part)])
         if h > 10 and rng.random() < 0.3:
             m.trim(s, m.pool.length(s) - int(rng.integers(1, 10)))
-    choices = [0, 1, 1, 2, 5, 9, 16, 17, 40, 64, 65, 130, 300, 700, 1030]
+    choices = [0, 1, 1, 2, 5, 9, 16, 17, 21, 24, 25, 40, 64, 65, 130, 300, 700, 1030]
     for turn in range(2):
         order = rng.permutation(n_slots).tolist()
         sl = [slots[i] for i in order]
