@@ -401,6 +401,7 @@ APPEND_ATTEND_CASES = {
     "small tile turn": (wl.PRODUCTION, [800], [[150], [150]]),
     "small stream step": (wl.PRODUCTION, [700, 0, 64], [[9, 1, 4], [1, 9, 16]]),
     "small tile and stream": (SMALL, [300, 20], [[40, 2], [3, 70]]),
+    "small stream step, three row blocks": (wl.PRODUCTION, [700, 0, 2000], [[24, 1, 17], [9, 21, 20]]),
 }
 
 
