@@ -228,6 +228,7 @@ constexpr int STREAM_ML_ROWS = STREAM_MAX_MB * 32;             // rows per wavef
 constexpr int STREAM_Q_OFFSET = STREAM_ML_OFFSET + 4 * STREAM_ML_ROWS * 2 * 4;
 constexpr int STREAM_NEXT_OFFSET = STREAM_Q_OFFSET + STREAM_MAX_MB * 32 * ROW_BYTES;
 constexpr int STREAM_LDS_BYTES = STREAM_NEXT_OFFSET + 128;
+static_assert(STREAM_LDS_BYTES <= 160 * 1024, "one workgroup per compute unit: all of its LDS, no more");
 
 // One wavefront moves 4 query rows (1 KiB) HBM -> LDS into the Q area: packed row `blk * 4 + l / 16` of the
 // unit (clamped to its last row), chunk slots swizzled as for a K tile so that read_k_frag serves as the
